@@ -1,0 +1,207 @@
+/*
+ * moe.h -- C ABI of the dynamically gated Mixture-of-Experts layer forward for
+ * AMD MI355X (gfx950), one GPU.
+ *
+ * The layer follows "Towards MoE Deployment: Mitigating Inefficiencies in
+ * Mixture-of-Expert (MoE) Inference": a linear gate picks the top-k experts of
+ * every token (Sec. 2.3, Sec. 2.4); with DYNAMIC gating (Sec. 5.1) the expert
+ * assignments are sorted by expert, the occurrences of each expert are counted,
+ * the tokens are reordered by the sort index into variable-sized per-expert
+ * batches (no capacity, no dropped token, no placeholder row), the experts run
+ * on exactly their rows, and the original order is restored by indexing.  The
+ * STATIC gating the paper replaces (Sec. 3.2, Sec. 5.1: fixed capacity per
+ * expert, one-hot dispatch masks multiplied with the tokens, drops and zero
+ * padding) is exported as a baseline for comparison.
+ *
+ * Conventions for every call
+ *   - Plain C.  Returns MOE_OK (0) or a negative MOE_ERR_* code; after an error
+ *     moe_last_error() gives a message (thread-local, valid until the next call
+ *     on the thread).  No exception crosses this boundary.
+ *   - Every tensor argument is a DEVICE pointer owned by the caller, row-major,
+ *     densely packed, 16-byte aligned.  The library allocates no device memory in
+ *     any call below; scratch comes from the caller's `workspace` (device memory,
+ *     256-byte aligned, at least moe_workspace_bytes() long; contents undefined
+ *     before and after a call; one workspace must not be used by two calls that
+ *     may overlap in time).
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
+ *     the default stream) and never wait for the device or read device data on
+ *     the host.  Argument errors are found on the host before anything is
+ *     launched.
+ *   - "elem" below is the storage type named by moe_config_t.dtype: float for
+ *     MOE_DTYPE_F32, bfloat16 bit patterns for MOE_DTYPE_BF16.  Accumulation is
+ *     always fp32; gate logits and gate weights are always fp32.
+ *   - Notation: T tokens, D = token (model) dimension, F = expert hidden
+ *     dimension, E experts, k experts per token, N = k*T assignments.
+ *   - Inputs must be finite.  Expert indices handed to moe_route_counts must lie
+ *     in [0,E); values outside are clamped into the range (memory safe, result
+ *     then meaningless).
+ */
+#ifndef MOE355_MOE_H
+#define MOE355_MOE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK 0
+#define MOE_ERR_INVALID_ARG (-1) /* NULL / misaligned pointer, T outside [0,T_max], bad size */
+#define MOE_ERR_UNSUPPORTED (-2) /* dtype, k, E, D or F outside the supported set */
+#define MOE_ERR_WORKSPACE (-3)   /* workspace missing or too small */
+#define MOE_ERR_HIP (-4)         /* the HIP runtime reported a failure */
+
+#define MOE_DTYPE_F32 0
+#define MOE_DTYPE_BF16 1
+
+#define MOE_STATIC_EINSUM 0  /* one-hot dispatch / combine masks multiplied as dense GEMMs */
+#define MOE_STATIC_INDEXED 1 /* same capacity, padding and drops, rows moved by index */
+
+#define MOE_CAPACITY_PAPER 0 /* capacity = ceil(cf * T): the paper's C*S */
+#define MOE_CAPACITY_SHARE 1 /* capacity = ceil(cf * k*T / E): cf times an expert's fair share */
+
+#define MOE_MAX_K 8
+#define MOE_MAX_E 1024
+
+/* Shape of the layer.  Supported: dtype in {F32, BF16}; 1 <= E <= MOE_MAX_E;
+ * 1 <= k <= min(E, MOE_MAX_K); D and F positive multiples of 8; T_max >= 0 with
+ * k*T_max < 2^31 / max(D,F) rows addressable in 64 bits (checked). */
+typedef struct moe_config {
+    int32_t T_max;       /* largest T any call on this handle will be given */
+    int32_t D;
+    int32_t F;
+    int32_t E;
+    int32_t k;
+    int32_t dtype;       /* MOE_DTYPE_* */
+    int32_t renormalize; /* 1: gate weights = softmax over the k selected logits (sum to 1);
+                            0: the k selected entries of the softmax over all E logits */
+} moe_config_t;
+
+typedef struct moe_handle moe_handle_t; /* opaque: the config plus device properties */
+
+/* Optional routing outputs of the fused calls; every member may be NULL. */
+typedef struct moe_routing {
+    float *logits;     /* [T,E]  */
+    int32_t *topk_idx; /* [T,k]  */
+    float *topk_w;     /* [T,k]  */
+    int32_t *counts;   /* [E]    */
+    int32_t *offsets;  /* [E+1]  */
+    int32_t *dst_row;  /* [T,k]  */
+    int32_t *src_tok;  /* [k*T]  */
+} moe_routing_t;
+
+/* Create / destroy a handle (host memory only).  moe_create validates the config
+ * (MOE_ERR_UNSUPPORTED / MOE_ERR_INVALID_ARG) and queries the current device
+ * (MOE_ERR_HIP when there is none). */
+int moe_create(const moe_config_t *cfg, moe_handle_t **out);
+int moe_destroy(moe_handle_t *h);
+
+/* Message of the last error on this thread ("" if none). */
+const char *moe_last_error(void);
+
+/* Per-kernel timing for benchmarks (Sec. 3.1 of the paper reports a latency breakdown by
+ * component; this is the tool that produces one here).  Between moe_profile_begin and
+ * moe_profile_end every kernel the calls on this handle launch is bracketed by HIP events
+ * recorded on the call's stream (at most 64 records; later launches are not recorded).
+ * moe_profile_end is the one call of this library that WAITS for the device: it waits for the
+ * recorded events, writes the elapsed milliseconds of record i to ms_out[i] (i < max_records),
+ * stores the number of records in *n_records and switches profiling off.  moe_profile_name
+ * gives the kernel name of record i ("" when out of range); valid until the next begin. */
+int moe_profile_begin(moe_handle_t *h);
+int moe_profile_end(moe_handle_t *h, float *ms_out, int32_t max_records, int32_t *n_records);
+const char *moe_profile_name(const moe_handle_t *h, int32_t i);
+
+/* Bytes of workspace that make every dynamic-gating call on this handle succeed for
+ * any T <= T_max (routing scratch, the dispatched rows Xp [N,D], the hidden rows
+ * H [N,F] and the expert outputs Yp [N,D]).  Negative error code on a bad handle. */
+int64_t moe_workspace_bytes(const moe_handle_t *h);
+
+/* Same for moe_layer_forward_static with the given T, capacity and mode. */
+int64_t moe_static_workspace_bytes(const moe_handle_t *h, int32_t T, int32_t capacity, int32_t mode);
+
+/* Rows per expert for a capacity factor cf under one of the two conventions
+ * (MOE_CAPACITY_PAPER: Sec. 3 / Sec. 5.1, capacity = C*S, e.g. S = 6, C = 0.5 -> 3;
+ * MOE_CAPACITY_SHARE: cf * k*T/E).  Negative error code on bad arguments. */
+int32_t moe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t convention);
+
+/* Gate + top-k routing decision (Sec. 2.3, Sec. 2.4).
+ *   logits[t,e] = sum_d x[t,d] * wg[e,d] (+ gate_bias[e]),  fp32
+ *   topk_idx[t,0..k-1] = the k experts with the largest logit, slot 0 the largest,
+ *                        equal logits to the lower expert index
+ *   topk_w[t,j] = gate weight of slot j (see moe_config_t.renormalize), fp32
+ * x [T,D] elem, wg [E,D] elem, gate_bias [E] fp32 or NULL.  logits_out [T,E] fp32 may
+ * be NULL only if `workspace` is given (the logits then live there).  workspace may be
+ * NULL when logits_out is given.  T = 0 is a no-op. */
+int moe_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias,
+                  int32_t T, float *logits_out, int32_t *topk_idx, float *topk_w,
+                  void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Routing metadata of dynamic gating (Sec. 5.1: the sort index of the expert
+ * assignments and the number of occurrences of each expert).
+ *   counts[e]    = number of (t,j) with topk_idx[t,j] = e                (sums to k*T)
+ *   offsets[e]   = counts[0] + ... + counts[e-1],  offsets[E] = k*T
+ *   dst_row[t,j] = offsets[e] + number of tokens t' < t that selected e,  e = topk_idx[t,j]
+ *   src_tok[r]   = the token whose assignment landed in row r (inverse of dst_row)
+ * The permutation is the stable one (ascending token inside each expert) and is
+ * computed without atomics on global memory, so it is identical from run to run.
+ * All arrays int32.  Needs the workspace.  T = 0 writes zero counts and offsets. */
+int moe_route_counts(moe_handle_t *h, const int32_t *topk_idx, int32_t T,
+                     int32_t *counts, int32_t *offsets, int32_t *dst_row, int32_t *src_tok,
+                     void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Dispatch (Sec. 5.1: reorder the inputs by the sort index; they are then split by the
+ * counts, i.e. rows [offsets[e], offsets[e+1]) of xp are expert e's batch):
+ *   xp[dst_row[t,j], :] = x[t, :]      x [T,D] elem -> xp [k*T, D] elem.
+ * Every row of xp is written exactly once; nothing is padded or dropped. */
+int moe_dispatch(moe_handle_t *h, const void *x, const int32_t *dst_row, int32_t T,
+                 void *xp, void *stream);
+
+/* Grouped expert FFN on the dispatched rows (Sec. 2.2 FFN block; each expert processes
+ * only the tokens assigned to it, Sec. 5.1):
+ *   for r in [offsets[e], offsets[e+1]):  yp[r,:] = W2[e] * relu(W1[e] * xp[r,:] + b1[e]) + b2[e]
+ * xp [N,D], w1 [E,F,D], w2 [E,D,F], b1 [E,F] or NULL, b2 [E,D] or NULL, yp [N,D], all elem;
+ * offsets [E+1] int32 on the device with offsets[E] = N = k*T, N given by the caller as
+ * n_rows (it sizes the launch; the device never reads more than offsets says).
+ * Experts with an empty range are skipped and their weights are never read.
+ * The hidden rows are rounded to elem once after the ReLU.  Needs the workspace. */
+int moe_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets,
+                   const void *w1, const void *w2, const void *b1, const void *b2,
+                   int32_t n_rows, void *yp, void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Combine (Sec. 5.1: restore the original order by indexing, weighted by the gate):
+ *   y[t,:] = sum_{j=0..k-1, in this order} topk_w[t,j] * yp[dst_row[t,j], :]
+ * accumulated in fp32 and rounded once.  yp [k*T,D] elem -> y [T,D] elem. */
+int moe_combine(moe_handle_t *h, const void *yp, const int32_t *dst_row, const float *topk_w,
+                int32_t T, void *y, void *stream);
+
+/* The whole dynamically gated layer: gate_topk -> route_counts -> dispatch ->
+ * expert_ffn -> combine, enqueued back to back on `stream` with no host
+ * synchronisation.  y [T,D] elem.  routing_out (may be NULL) receives the routing
+ * arrays whose members are non-NULL. */
+int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias,
+                      const void *w1, const void *w2, const void *b1, const void *b2,
+                      int32_t T, void *y, const moe_routing_t *routing_out,
+                      void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Static-capacity baseline (Sec. 3.2, Sec. 5.1): same gate; every expert owns
+ * `capacity` rows; assignments are placed slot by slot (all first choices in token
+ * order, then all second choices, ...) into the first empty row of their expert and
+ * are DROPPED when the expert is full (they then contribute nothing; gate weights are
+ * not renormalised); unused rows are zero and the experts still process all
+ * E*capacity rows.
+ *   MOE_STATIC_EINSUM : dispatch = one-hot mask [E*cap, T] times x, combine = weight
+ *                       mask [T, E*cap] times the expert outputs, both as dense GEMMs
+ *                       (the formulation the paper identifies as the inefficiency);
+ *   MOE_STATIC_INDEXED: same rows, moved by index.
+ * dropped_count (device int32, may be NULL) receives the number of dropped assignments.
+ * Workspace: moe_static_workspace_bytes(). */
+int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias,
+                             const void *w1, const void *w2, const void *b1, const void *b2,
+                             int32_t T, int32_t capacity, int32_t mode, void *y,
+                             int32_t *dropped_count, const moe_routing_t *routing_out,
+                             void *workspace, int64_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE355_MOE_H */

@@ -84,6 +84,15 @@ static double dot_fb(const float *a, const uint16_t *b, int n)
     return acc;
 }
 
+static double dot_bb(const uint16_t *a, const uint16_t *b, int n)
+{
+    double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+    for (int i = 0; i < n; ++i)
+        acc += (double)bf16_to_f32(a[i]) * (double)bf16_to_f32(b[i]);
+    return acc;
+}
+
 static double dot_db(const double *a, const uint16_t *b, int n)
 {
     double acc = 0.0;
@@ -101,9 +110,8 @@ void moe_oracle_gate_logits(const void *x, const void *wg, const float *bias,
 #pragma omp parallel for schedule(static)
     for (int t = 0; t < T; ++t) {
         for (int e = 0; e < E; ++e) {
-            double acc = 0.0;
-            for (int d = 0; d < D; ++d)
-                acc += ld(x, (size_t)t * D + d, dt) * ld(wg, (size_t)e * D + d, dt);
+            double acc = dt == 0 ? dot_ff((const float *)x + (size_t)t * D, (const float *)wg + (size_t)e * D, D)
+                                 : dot_bb((const uint16_t *)x + (size_t)t * D, (const uint16_t *)wg + (size_t)e * D, D);
             if (bias)
                 acc += (double)bias[e];
             logits[(size_t)t * E + e] = (float)acc;

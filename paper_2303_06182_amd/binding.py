@@ -1,0 +1,268 @@
+"""Thin Python binding of libmoe355 (include/moe.h): argument marshalling only.
+
+Every step of the layer runs in the library's HIP kernels; torch is used for device
+memory (tensors own the buffers) and for the current stream.  If the library has not been
+built the import of this module's functions raises -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe355.so")
+
+MOE_OK = 0
+MOE_ERR_INVALID_ARG = -1
+MOE_ERR_UNSUPPORTED = -2
+MOE_ERR_WORKSPACE = -3
+MOE_ERR_HIP = -4
+MOE_DTYPE_F32 = 0
+MOE_DTYPE_BF16 = 1
+MOE_STATIC_EINSUM = 0
+MOE_STATIC_INDEXED = 1
+MOE_CAPACITY_PAPER = 0
+MOE_CAPACITY_SHARE = 1
+
+EXPORTS = [
+    "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_static_workspace_bytes",
+    "moe_capacity", "moe_gate_topk", "moe_route_counts", "moe_dispatch", "moe_expert_ffn", "moe_combine",
+    "moe_layer_forward", "moe_layer_forward_static", "moe_profile_begin", "moe_profile_end", "moe_profile_name",
+]
+
+
+class MoeConfig(ctypes.Structure):
+    _fields_ = [("T_max", ctypes.c_int32), ("D", ctypes.c_int32), ("F", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("renormalize", ctypes.c_int32)]
+
+
+class MoeRouting(ctypes.Structure):
+    _fields_ = [("logits", ctypes.c_void_p), ("topk_idx", ctypes.c_void_p), ("topk_w", ctypes.c_void_p),
+                ("counts", ctypes.c_void_p), ("offsets", ctypes.c_void_p), ("dst_row", ctypes.c_void_p),
+                ("src_tok", ctypes.c_void_p)]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("libmoe355 error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmoe355.so (built by paper_2303_06182_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libmoe355.so is not built (run `python -m paper_2303_06182_amd.build`); "
+                           "there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.moe_create.argtypes = [ctypes.POINTER(MoeConfig), ctypes.POINTER(vp)]
+    lib.moe_create.restype = ctypes.c_int
+    lib.moe_destroy.argtypes = [vp]
+    lib.moe_destroy.restype = ctypes.c_int
+    lib.moe_last_error.argtypes = []
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_workspace_bytes.argtypes = [vp]
+    lib.moe_workspace_bytes.restype = i64
+    lib.moe_static_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.moe_static_workspace_bytes.restype = i64
+    lib.moe_capacity.argtypes = [i32, i32, i32, ctypes.c_double, i32]
+    lib.moe_capacity.restype = i32
+    lib.moe_gate_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, i64, vp]
+    lib.moe_gate_topk.restype = ctypes.c_int
+    lib.moe_route_counts.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, i64, vp]
+    lib.moe_route_counts.restype = ctypes.c_int
+    lib.moe_dispatch.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.moe_dispatch.restype = ctypes.c_int
+    lib.moe_expert_ffn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i64, vp]
+    lib.moe_expert_ffn.restype = ctypes.c_int
+    lib.moe_combine.argtypes = [vp, vp, vp, vp, i32, vp, vp]
+    lib.moe_combine.restype = ctypes.c_int
+    lib.moe_layer_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting), vp, i64, vp]
+    lib.moe_layer_forward.restype = ctypes.c_int
+    lib.moe_layer_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp,
+                                             ctypes.POINTER(MoeRouting), vp, i64, vp]
+    lib.moe_layer_forward_static.restype = ctypes.c_int
+    lib.moe_profile_begin.argtypes = [vp]
+    lib.moe_profile_begin.restype = ctypes.c_int
+    lib.moe_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
+    lib.moe_profile_end.restype = ctypes.c_int
+    lib.moe_profile_name.argtypes = [vp, i32]
+    lib.moe_profile_name.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != MOE_OK:
+        raise MoeError(rc, load_library().moe_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def moe_capacity(T: int, E: int, k: int, cf: float, convention: int = MOE_CAPACITY_SHARE) -> int:
+    c = load_library().moe_capacity(T, E, k, cf, convention)
+    if c < 0:
+        _check(c)
+    return c
+
+
+class MoeLayer:
+    """A handle (moe_create) plus a workspace tensor.  Methods mirror the C entry points and
+    only marshal arguments; outputs are allocated by the caller or, for convenience, here
+    (torch.empty) before the call."""
+
+    def __init__(self, T_max: int, D: int, F: int, E: int, k: int = 2, dtype: str = "bf16",
+                 renormalize: bool = True, device: str = "cuda:0", alloc_workspace: bool = True):
+        self.lib = load_library()
+        self.cfg = MoeConfig(T_max, D, F, E, k, MOE_DTYPE_BF16 if dtype == "bf16" else MOE_DTYPE_F32,
+                             int(renormalize))
+        self.T_max, self.D, self.F, self.E, self.k = T_max, D, F, E, k
+        self.dtype = dtype
+        self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.device = torch.device(device)
+        h = ctypes.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.lib.moe_create(ctypes.byref(self.cfg), ctypes.byref(h)))
+        self.h = h
+        self.workspace_bytes = int(self.lib.moe_workspace_bytes(self.h))
+        self.workspace = None
+        if alloc_workspace:
+            self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+
+    def __del__(self):
+        try:
+            if getattr(self, "h", None):
+                self.lib.moe_destroy(self.h)
+                self.h = None
+        except Exception:
+            pass
+
+    # -- helpers ---------------------------------------------------------------------------
+    def _ws(self):
+        if self.workspace is None:
+            return None, 0
+        return _ptr(self.workspace), self.workspace.numel()
+
+    def _new(self, shape, dtype):
+        return torch.empty(shape, dtype=dtype, device=self.device)
+
+    def empty_routing(self, T: int) -> dict:
+        return dict(logits=self._new((T, self.E), torch.float32), topk_idx=self._new((T, self.k), torch.int32),
+                    topk_w=self._new((T, self.k), torch.float32), counts=self._new((self.E,), torch.int32),
+                    offsets=self._new((self.E + 1,), torch.int32), dst_row=self._new((T, self.k), torch.int32),
+                    src_tok=self._new((T * self.k,), torch.int32))
+
+    @staticmethod
+    def _routing_struct(r: Optional[dict]):
+        if r is None:
+            return None
+        s = MoeRouting()
+        for name in ("logits", "topk_idx", "topk_w", "counts", "offsets", "dst_row", "src_tok"):
+            t = r.get(name)
+            setattr(s, name, None if t is None else t.data_ptr())
+        return ctypes.byref(s)
+
+    # -- the entry points ------------------------------------------------------------------
+    def moe_gate_topk(self, x, wg, gate_bias=None, logits_out=None, topk_idx=None, topk_w=None):
+        T = x.shape[0]
+        if logits_out is None:
+            logits_out = self._new((T, self.E), torch.float32)
+        if topk_idx is None:
+            topk_idx = self._new((T, self.k), torch.int32)
+        if topk_w is None:
+            topk_w = self._new((T, self.k), torch.float32)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_gate_topk(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), T, _ptr(logits_out),
+                                      _ptr(topk_idx), _ptr(topk_w), ws, wsb, _stream()))
+        return logits_out, topk_idx, topk_w
+
+    def moe_route_counts(self, topk_idx):
+        T = topk_idx.shape[0]
+        counts = self._new((self.E,), torch.int32)
+        offsets = self._new((self.E + 1,), torch.int32)
+        dst_row = self._new((T, self.k), torch.int32)
+        src_tok = self._new((T * self.k,), torch.int32)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_route_counts(self.h, _ptr(topk_idx), T, _ptr(counts), _ptr(offsets), _ptr(dst_row),
+                                         _ptr(src_tok), ws, wsb, _stream()))
+        return counts, offsets, dst_row, src_tok
+
+    def moe_dispatch(self, x, dst_row):
+        T = x.shape[0]
+        xp = self._new((T * self.k, self.D), self.torch_dtype)
+        _check(self.lib.moe_dispatch(self.h, _ptr(x), _ptr(dst_row), T, _ptr(xp), _stream()))
+        return xp
+
+    def moe_expert_ffn(self, xp, offsets, w1, w2, b1=None, b2=None):
+        n_rows = xp.shape[0]
+        yp = self._new((n_rows, self.D), self.torch_dtype)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_expert_ffn(self.h, _ptr(xp), _ptr(offsets), _ptr(w1), _ptr(w2), _ptr(b1), _ptr(b2),
+                                       n_rows, _ptr(yp), ws, wsb, _stream()))
+        return yp
+
+    def moe_combine(self, yp, dst_row, topk_w):
+        T = dst_row.shape[0]
+        y = self._new((T, self.D), self.torch_dtype)
+        _check(self.lib.moe_combine(self.h, _ptr(yp), _ptr(dst_row), _ptr(topk_w), T, _ptr(y), _stream()))
+        return y
+
+    def moe_layer_forward(self, x, wg, w1, w2, gate_bias=None, b1=None, b2=None, y=None, routing_out=None):
+        T = x.shape[0]
+        if y is None:
+            y = self._new((T, self.D), self.torch_dtype)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_layer_forward(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1), _ptr(w2), _ptr(b1),
+                                          _ptr(b2), T, _ptr(y), self._routing_struct(routing_out), ws, wsb,
+                                          _stream()))
+        return y
+
+    def moe_profile_begin(self) -> None:
+        _check(self.lib.moe_profile_begin(self.h))
+
+    def moe_profile_end(self):
+        """-> list of (kernel name, milliseconds) in launch order.  Waits for the device."""
+        ms = (ctypes.c_float * 64)()
+        n = ctypes.c_int32(0)
+        _check(self.lib.moe_profile_end(self.h, ms, 64, ctypes.byref(n)))
+        return [(self.lib.moe_profile_name(self.h, i).decode(), float(ms[i])) for i in range(n.value)]
+
+    def moe_static_workspace_bytes(self, T: int, capacity: int, mode: int) -> int:
+        n = int(self.lib.moe_static_workspace_bytes(self.h, T, capacity, mode))
+        if n < 0:
+            _check(n)
+        return n
+
+    def moe_layer_forward_static(self, x, wg, w1, w2, capacity: int, mode: int = MOE_STATIC_INDEXED,
+                                 gate_bias=None, b1=None, b2=None, y=None, routing_out=None, workspace=None):
+        T = x.shape[0]
+        if y is None:
+            y = self._new((T, self.D), self.torch_dtype)
+        dropped = torch.zeros(4, dtype=torch.int32, device=self.device)
+        if workspace is None:
+            workspace = torch.empty(self.moe_static_workspace_bytes(T, capacity, mode), dtype=torch.uint8,
+                                    device=self.device)
+        _check(self.lib.moe_layer_forward_static(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1), _ptr(w2),
+                                                 _ptr(b1), _ptr(b2), T, capacity, mode, _ptr(y), _ptr(dropped),
+                                                 self._routing_struct(routing_out), _ptr(workspace),
+                                                 workspace.numel(), _stream()))
+        return y, dropped[:1]

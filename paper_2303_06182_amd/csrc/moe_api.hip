@@ -1,0 +1,527 @@
+// C-ABI entry points of libmoe355 (declared in include/moe.h): argument validation on the host,
+// workspace carving, and the launch sequences.  No entry point allocates device memory, waits
+// for the device, or reads device data on the host.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "moe_internal.h"
+
+namespace moe355 {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_failed(hipError_t e, const char *what)
+{
+    set_error("HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
+    return MOE_ERR_HIP;
+}
+
+// ---- per-kernel event timing ---------------------------------------------------------------------
+static thread_local Profiler *g_prof = nullptr;
+
+ProfBind::ProfBind(moe_handle *h) { g_prof = (h && h->prof.enabled) ? &h->prof : nullptr; }
+ProfBind::~ProfBind() { g_prof = nullptr; }
+
+ProfScope::ProfScope(const char *name, hipStream_t s) : stream(s), slot(-1)
+{
+    Profiler *p = g_prof;
+    if (!p || p->n >= Profiler::kMax) return;
+    while (p->created <= p->n) {
+        if (hipEventCreate(&p->start[p->created]) != hipSuccess) return;
+        if (hipEventCreate(&p->stop[p->created]) != hipSuccess) {
+            (void)hipEventDestroy(p->start[p->created]);
+            return;
+        }
+        p->created += 1;
+    }
+    slot = p->n++;
+    p->names[slot] = name;
+    (void)hipEventRecord(p->start[slot], stream);
+}
+
+ProfScope::~ProfScope()
+{
+    if (slot >= 0 && g_prof) (void)hipEventRecord(g_prof->stop[slot], stream);
+}
+
+int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, hipStream_t s);
+int gemm_bf16_block_m(int64_t n_rows, int E);
+int launch_gemm_f32(const GemmParams &p, bool grouped, int block_m, bool relu, hipStream_t s);
+
+int gemm_block_m(int dtype, int64_t n_rows, int E)
+{
+    return dtype == MOE_DTYPE_BF16 ? gemm_bf16_block_m(n_rows, E) : 64;
+}
+
+int launch_gemm(int dtype, const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
+                hipStream_t s)
+{
+    (void)num_cus;
+    ProfScope ps(!grouped ? "gate_gemm" : (relu ? "expert_gemm1" : "expert_gemm2"), s);
+    if (dtype == MOE_DTYPE_BF16) return launch_gemm_bf16(p, grouped, block_m, out_f32, relu, s);
+    return launch_gemm_f32(p, grouped, block_m, relu, s);  // fp32 storage: C is fp32 either way
+}
+
+// ---- workspace ---------------------------------------------------------------------------------
+static constexpr int kMinBlockM = 32;  // smallest M tile any grouped GEMM uses: sizes the tile map
+
+struct WsLayout {
+    int64_t logits, topk_idx, topk_w, counts, offsets, dst_row, src_tok, block_hist;
+    int64_t tile_expert, tile_row, num_tiles, xp, h, yp, total;
+};
+
+static int elem_size(int dtype) { return dtype == MOE_DTYPE_BF16 ? 2 : 4; }
+
+static WsLayout ws_layout(const moe_config_t &c)
+{
+    WsLayout L;
+    const int64_t T = c.T_max, N = (int64_t)c.T_max * c.k, E = c.E, es = elem_size(c.dtype);
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        const int64_t at = off;
+        off = align_up(off + (bytes > 0 ? bytes : 1), 256);
+        return at;
+    };
+    L.logits = take(T * E * 4);
+    L.topk_idx = take(N * 4);
+    L.topk_w = take(N * 4);
+    L.counts = take(E * 4);
+    L.offsets = take((E + 1) * 4);
+    L.dst_row = take(N * 4);
+    L.src_tok = take(N * 4);
+    L.block_hist = take((int64_t)route_blocks((int)T) * E * 4);
+    const int64_t max_tiles = N / kMinBlockM + E + 1;
+    L.tile_expert = take(max_tiles * 4);
+    L.tile_row = take(max_tiles * 4);
+    L.num_tiles = take(4);
+    L.xp = take(N * c.D * es);
+    L.h = take(N * c.F * es);
+    L.yp = take(N * c.D * es);
+    L.total = off;
+    return L;
+}
+
+template <typename T>
+static T *at(void *ws, int64_t off)
+{
+    return reinterpret_cast<T *>(static_cast<uint8_t *>(ws) + off);
+}
+
+// ---- validation --------------------------------------------------------------------------------
+static bool bad_ptr(const void *p, const char *name, bool nullable = false)
+{
+    if (!p) {
+        if (nullable) return false;
+        set_error("%s is NULL", name);
+        return true;
+    }
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) {
+        set_error("%s is not 16-byte aligned", name);
+        return true;
+    }
+    return false;
+}
+
+static int check_handle_T(const moe_handle_t *h, int32_t T)
+{
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (T < 0 || T > h->cfg.T_max) {
+        set_error("T = %d outside [0, T_max = %d]", T, h->cfg.T_max);
+        return MOE_ERR_INVALID_ARG;
+    }
+    return MOE_OK;
+}
+
+static int check_ws(const moe_handle_t *h, const void *ws, int64_t bytes)
+{
+    if (!ws) {
+        set_error("workspace is NULL");
+        return MOE_ERR_WORKSPACE;
+    }
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) {
+        set_error("workspace is not 256-byte aligned");
+        return MOE_ERR_WORKSPACE;
+    }
+    const int64_t need = ws_layout(h->cfg).total;
+    if (bytes < need) {
+        set_error("workspace has %lld bytes, %lld needed", (long long)bytes, (long long)need);
+        return MOE_ERR_WORKSPACE;
+    }
+    return MOE_OK;
+}
+
+static int validate_config(const moe_config_t *c)
+{
+    if (!c) {
+        set_error("config is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (c->dtype != MOE_DTYPE_F32 && c->dtype != MOE_DTYPE_BF16) {
+        set_error("unsupported dtype %d", c->dtype);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (c->E < 1 || c->E > MOE_MAX_E) {
+        set_error("E = %d outside [1, %d]", c->E, MOE_MAX_E);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (c->k < 1 || c->k > MOE_MAX_K || c->k > c->E) {
+        set_error("k = %d outside [1, min(E, %d)]", c->k, MOE_MAX_K);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (c->D < 8 || c->D % 8 != 0 || c->F < 8 || c->F % 8 != 0) {
+        set_error("D = %d and F = %d must be positive multiples of 8", c->D, c->F);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (c->T_max < 0) {
+        set_error("T_max = %d is negative", c->T_max);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if ((int64_t)c->T_max * c->k > 0x3fffffff) {
+        set_error("k * T_max = %lld does not fit the int32 row indices", (long long)c->T_max * c->k);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (c->renormalize != 0 && c->renormalize != 1) {
+        set_error("renormalize must be 0 or 1");
+        return MOE_ERR_INVALID_ARG;
+    }
+    return MOE_OK;
+}
+
+// ---- the five steps ------------------------------------------------------------------------------
+static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, int T,
+                        float *logits, int32_t *idx, float *w, hipStream_t s)
+{
+    const moe_config_t &c = h->cfg;
+    if (T == 0) return MOE_OK;
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A = x;
+    p.lda = c.D;
+    p.B = wg;
+    p.ldb = c.D;
+    p.bias_f32 = gate_bias;
+    p.C = logits;
+    p.ldc = c.E;
+    p.M = T;
+    p.N = c.E;
+    p.K = c.D;
+    int rc = launch_gemm(c.dtype, p, false, 0, true, false, h->num_cus, s);
+    if (rc != MOE_OK) return rc;
+    return launch_topk(logits, T, c.E, c.k, c.renormalize, idx, w, s);
+}
+
+static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
+                         const void *b1, const void *b2, int n_rows, void *yp, void *ws, hipStream_t s)
+{
+    const moe_config_t &c = h->cfg;
+    if (n_rows == 0) return MOE_OK;
+    const WsLayout L = ws_layout(c);
+    const int bm = gemm_block_m(c.dtype, n_rows, c.E);
+    const int max_tiles = n_rows / bm + c.E + 1;
+    int32_t *tile_expert = at<int32_t>(ws, L.tile_expert);
+    int32_t *tile_row = at<int32_t>(ws, L.tile_row);
+    int32_t *num_tiles = at<int32_t>(ws, L.num_tiles);
+    int rc = launch_tile_map(offsets, c.E, bm, tile_expert, tile_row, num_tiles, max_tiles, s);
+    if (rc != MOE_OK) return rc;
+
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.offsets = offsets;
+    p.tile_expert = tile_expert;
+    p.tile_row = tile_row;
+    p.num_tiles = num_tiles;
+    p.max_m_tiles = max_tiles;
+    p.M = n_rows;
+    // H = relu(Xp * W1[e]^T + b1[e])
+    p.A = xp;
+    p.lda = c.D;
+    p.B = w1;
+    p.ldb = c.D;
+    p.strideB = (int64_t)c.F * c.D;
+    p.bias = b1;
+    p.strideBias = c.F;
+    p.C = at<void>(ws, L.h);
+    p.ldc = c.F;
+    p.N = c.F;
+    p.K = c.D;
+    rc = launch_gemm(c.dtype, p, true, bm, false, true, h->num_cus, s);
+    if (rc != MOE_OK) return rc;
+    // Yp = H * W2[e]^T + b2[e]
+    p.A = at<void>(ws, L.h);
+    p.lda = c.F;
+    p.B = w2;
+    p.ldb = c.F;
+    p.strideB = (int64_t)c.D * c.F;
+    p.bias = b2;
+    p.strideBias = c.D;
+    p.C = yp;
+    p.ldc = c.D;
+    p.N = c.D;
+    p.K = c.F;
+    return launch_gemm(c.dtype, p, true, bm, false, false, h->num_cus, s);
+}
+
+}  // namespace moe355
+
+using namespace moe355;
+
+extern "C" {
+
+const char *moe_last_error(void) { return g_err; }
+
+int moe_create(const moe_config_t *cfg, moe_handle_t **out)
+{
+    g_err[0] = 0;
+    if (!out) {
+        set_error("out is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    *out = nullptr;
+    int rc = validate_config(cfg);
+    if (rc != MOE_OK) return rc;
+    int dev = 0;
+    MOE_HIP_CHECK(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    MOE_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
+    moe_handle_t *h = new (std::nothrow) moe_handle_t;
+    if (!h) {
+        set_error("out of host memory");
+        return MOE_ERR_INVALID_ARG;
+    }
+    h->cfg = *cfg;
+    h->device = dev;
+    h->num_cus = prop.multiProcessorCount;
+    *out = h;
+    return MOE_OK;
+}
+
+int moe_destroy(moe_handle_t *h)
+{
+    if (h) {
+        for (int i = 0; i < h->prof.created; ++i) {
+            (void)hipEventDestroy(h->prof.start[i]);
+            (void)hipEventDestroy(h->prof.stop[i]);
+        }
+    }
+    delete h;
+    return MOE_OK;
+}
+
+int moe_profile_begin(moe_handle_t *h)
+{
+    g_err[0] = 0;
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    h->prof.enabled = true;
+    h->prof.n = 0;
+    return MOE_OK;
+}
+
+int moe_profile_end(moe_handle_t *h, float *ms_out, int32_t max_records, int32_t *n_records)
+{
+    g_err[0] = 0;
+    if (!h || !n_records || (max_records > 0 && !ms_out)) {
+        set_error("moe_profile_end: NULL argument");
+        return MOE_ERR_INVALID_ARG;
+    }
+    Profiler &p = h->prof;
+    p.enabled = false;
+    const int n = p.n < max_records ? p.n : max_records;
+    for (int i = 0; i < n; ++i) {
+        MOE_HIP_CHECK(hipEventSynchronize(p.stop[i]));
+        MOE_HIP_CHECK(hipEventElapsedTime(&ms_out[i], p.start[i], p.stop[i]));
+    }
+    *n_records = n;
+    return MOE_OK;
+}
+
+const char *moe_profile_name(const moe_handle_t *h, int32_t i)
+{
+    if (!h || i < 0 || i >= h->prof.n) return "";
+    return h->prof.names[i];
+}
+
+int64_t moe_workspace_bytes(const moe_handle_t *h)
+{
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    return ws_layout(h->cfg).total;
+}
+
+int32_t moe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t convention)
+{
+    if (T < 0 || E < 1 || k < 1 || !(cf > 0.0)) {
+        set_error("moe_capacity: bad arguments");
+        return MOE_ERR_INVALID_ARG;
+    }
+    double rows;
+    if (convention == MOE_CAPACITY_PAPER)
+        rows = cf * (double)T;
+    else if (convention == MOE_CAPACITY_SHARE)
+        rows = cf * (double)k * (double)T / (double)E;
+    else {
+        set_error("moe_capacity: unknown convention %d", convention);
+        return MOE_ERR_INVALID_ARG;
+    }
+    int64_t c = (int64_t)rows;
+    if ((double)c < rows - 1e-9) c += 1;
+    if (c > 0x7fffffff) {
+        set_error("moe_capacity: result does not fit int32");
+        return MOE_ERR_INVALID_ARG;
+    }
+    return (int32_t)c;
+}
+
+int moe_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, int32_t T,
+                  float *logits_out, int32_t *topk_idx, float *topk_w, void *workspace, int64_t workspace_bytes,
+                  void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    int rc = check_handle_T(h, T);
+    if (rc != MOE_OK) return rc;
+    if (T == 0) return MOE_OK;
+    if (bad_ptr(x, "x") || bad_ptr(wg, "wg") || bad_ptr(gate_bias, "gate_bias", true) ||
+        bad_ptr(logits_out, "logits_out", true) || bad_ptr(topk_idx, "topk_idx") || bad_ptr(topk_w, "topk_w"))
+        return MOE_ERR_INVALID_ARG;
+    float *logits = logits_out;
+    if (!logits) {
+        rc = check_ws(h, workspace, workspace_bytes);
+        if (rc != MOE_OK) return rc;
+        logits = at<float>(workspace, ws_layout(h->cfg).logits);
+    }
+    return do_gate_topk(h, x, wg, gate_bias, T, logits, topk_idx, topk_w, (hipStream_t)stream);
+}
+
+int moe_route_counts(moe_handle_t *h, const int32_t *topk_idx, int32_t T, int32_t *counts, int32_t *offsets,
+                     int32_t *dst_row, int32_t *src_tok, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    int rc = check_handle_T(h, T);
+    if (rc != MOE_OK) return rc;
+    const bool empty = (T == 0);  // nothing but counts and offsets is touched then
+    if (bad_ptr(topk_idx, "topk_idx", empty) || bad_ptr(counts, "counts") || bad_ptr(offsets, "offsets") ||
+        bad_ptr(dst_row, "dst_row", empty) || bad_ptr(src_tok, "src_tok", empty))
+        return MOE_ERR_INVALID_ARG;
+    rc = check_ws(h, workspace, workspace_bytes);
+    if (rc != MOE_OK) return rc;
+    return launch_route(topk_idx, T, h->cfg.E, h->cfg.k, counts, offsets, dst_row, src_tok,
+                        at<int32_t>(workspace, ws_layout(h->cfg).block_hist), (hipStream_t)stream);
+}
+
+int moe_dispatch(moe_handle_t *h, const void *x, const int32_t *dst_row, int32_t T, void *xp, void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    int rc = check_handle_T(h, T);
+    if (rc != MOE_OK) return rc;
+    if (T == 0) return MOE_OK;
+    if (bad_ptr(x, "x") || bad_ptr(dst_row, "dst_row") || bad_ptr(xp, "xp")) return MOE_ERR_INVALID_ARG;
+    return launch_dispatch(h->cfg.dtype, x, dst_row, T, h->cfg.D, h->cfg.k, xp, (hipStream_t)stream);
+}
+
+int moe_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
+                   const void *b1, const void *b2, int32_t n_rows, void *yp, void *workspace,
+                   int64_t workspace_bytes, void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (n_rows < 0 || (int64_t)n_rows > (int64_t)h->cfg.T_max * h->cfg.k) {
+        set_error("n_rows = %d outside [0, k*T_max = %lld]", n_rows, (long long)h->cfg.T_max * h->cfg.k);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (n_rows == 0) return MOE_OK;
+    if (bad_ptr(xp, "xp") || bad_ptr(offsets, "offsets") || bad_ptr(w1, "w1") || bad_ptr(w2, "w2") ||
+        bad_ptr(b1, "b1", true) || bad_ptr(b2, "b2", true) || bad_ptr(yp, "yp"))
+        return MOE_ERR_INVALID_ARG;
+    int rc = check_ws(h, workspace, workspace_bytes);
+    if (rc != MOE_OK) return rc;
+    return do_expert_ffn(h, xp, offsets, w1, w2, b1, b2, n_rows, yp, workspace, (hipStream_t)stream);
+}
+
+int moe_combine(moe_handle_t *h, const void *yp, const int32_t *dst_row, const float *topk_w, int32_t T, void *y,
+                void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    int rc = check_handle_T(h, T);
+    if (rc != MOE_OK) return rc;
+    if (T == 0) return MOE_OK;
+    if (bad_ptr(yp, "yp") || bad_ptr(dst_row, "dst_row") || bad_ptr(topk_w, "topk_w") || bad_ptr(y, "y"))
+        return MOE_ERR_INVALID_ARG;
+    return launch_combine(h->cfg.dtype, yp, dst_row, topk_w, T, h->cfg.D, h->cfg.k, y, (hipStream_t)stream);
+}
+
+int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1,
+                      const void *w2, const void *b1, const void *b2, int32_t T, void *y,
+                      const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    int rc = check_handle_T(h, T);
+    if (rc != MOE_OK) return rc;
+    const bool empty = (T == 0);  // only counts and offsets are written then
+    if (bad_ptr(x, "x", empty) || bad_ptr(wg, "wg", empty) || bad_ptr(gate_bias, "gate_bias", true) ||
+        bad_ptr(w1, "w1", empty) || bad_ptr(w2, "w2", empty) || bad_ptr(b1, "b1", true) || bad_ptr(b2, "b2", true) ||
+        bad_ptr(y, "y", empty))
+        return MOE_ERR_INVALID_ARG;
+    moe_routing_t r;
+    memset(&r, 0, sizeof(r));
+    if (routing_out) r = *routing_out;
+    if (bad_ptr(r.logits, "routing_out.logits", true) || bad_ptr(r.topk_idx, "routing_out.topk_idx", true) ||
+        bad_ptr(r.topk_w, "routing_out.topk_w", true) || bad_ptr(r.counts, "routing_out.counts", true) ||
+        bad_ptr(r.offsets, "routing_out.offsets", true) || bad_ptr(r.dst_row, "routing_out.dst_row", true) ||
+        bad_ptr(r.src_tok, "routing_out.src_tok", true))
+        return MOE_ERR_INVALID_ARG;
+    rc = check_ws(h, workspace, workspace_bytes);
+    if (rc != MOE_OK) return rc;
+    const moe_config_t &c = h->cfg;
+    const WsLayout L = ws_layout(c);
+    hipStream_t s = (hipStream_t)stream;
+    float *logits = r.logits ? r.logits : at<float>(workspace, L.logits);
+    int32_t *idx = r.topk_idx ? r.topk_idx : at<int32_t>(workspace, L.topk_idx);
+    float *w = r.topk_w ? r.topk_w : at<float>(workspace, L.topk_w);
+    int32_t *counts = r.counts ? r.counts : at<int32_t>(workspace, L.counts);
+    int32_t *offsets = r.offsets ? r.offsets : at<int32_t>(workspace, L.offsets);
+    int32_t *dst_row = r.dst_row ? r.dst_row : at<int32_t>(workspace, L.dst_row);
+    int32_t *src_tok = r.src_tok ? r.src_tok : at<int32_t>(workspace, L.src_tok);
+    void *xp = at<void>(workspace, L.xp);
+    void *yp = at<void>(workspace, L.yp);
+
+    if (empty) return launch_route(idx, 0, c.E, c.k, counts, offsets, dst_row, src_tok,
+                                   at<int32_t>(workspace, L.block_hist), s);
+    rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, at<int32_t>(workspace, L.block_hist), s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_dispatch(c.dtype, x, dst_row, T, c.D, c.k, xp, s);
+    if (rc != MOE_OK) return rc;
+    rc = do_expert_ffn(h, xp, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
+    if (rc != MOE_OK) return rc;
+    return launch_combine(c.dtype, yp, dst_row, w, T, c.D, c.k, y, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,111 @@
+// Internal declarations shared by the HIP translation units of libmoe355.
+// Nothing here is part of the C ABI (include/moe.h is).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe355 {
+// Optional per-kernel timing with HIP events recorded on the stream the kernels run on.
+struct Profiler {
+    static constexpr int kMax = 64;
+    bool enabled = false;
+    int n = 0;
+    const char *names[kMax];
+    hipEvent_t start[kMax];
+    hipEvent_t stop[kMax];
+    int created = 0;  // events [0, created) exist
+};
+}  // namespace moe355
+
+struct moe_handle {
+    moe_config_t cfg;
+    int device;
+    int num_cus;
+    moe355::Profiler prof;
+};
+
+namespace moe355 {
+
+// ---- errors -----------------------------------------------------------------------------------
+void set_error(const char *fmt, ...);
+int hip_failed(hipError_t e, const char *what);  // records the message, returns MOE_ERR_HIP
+#define MOE_HIP_CHECK(expr)                                                  \
+    do {                                                                     \
+        hipError_t _e = (expr);                                              \
+        if (_e != hipSuccess) return ::moe355::hip_failed(_e, #expr);        \
+    } while (0)
+#define MOE_LAUNCH_CHECK(name)                                               \
+    do {                                                                     \
+        hipError_t _e = hipGetLastError();                                   \
+        if (_e != hipSuccess) return ::moe355::hip_failed(_e, name);         \
+    } while (0)
+
+// Brackets one kernel launch with events when the calling entry point's handle has profiling on.
+struct ProfScope {
+    ProfScope(const char *name, hipStream_t s);
+    ~ProfScope();
+    hipStream_t stream;
+    int slot;
+};
+// Binds the handle's profiler to the calling thread for the duration of an entry point.
+struct ProfBind {
+    explicit ProfBind(moe_handle *h);
+    ~ProfBind();
+};
+
+__host__ __device__ static inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+__host__ __device__ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---- grouped / plain GEMM  C = A * B^T  (both operands K-contiguous) ---------------------------
+// Plain mode: one problem of M rows.  Grouped mode: rows [offsets[e], offsets[e+1]) of A use
+// B + e*strideB; M tiles never straddle two experts (the tile map says which expert and which
+// first row every M tile has).
+struct GemmParams {
+    const void *A;       // [rows, K]
+    int64_t lda;
+    const void *B;       // [N, K] (plain) or [E, N, K] (grouped)
+    int64_t ldb;
+    int64_t strideB;     // elements between experts
+    const void *bias;    // elem [N] / [E,N], or NULL
+    int64_t strideBias;
+    const float *bias_f32;  // fp32 [N] or NULL (gate offsets)
+    void *C;             // [rows, N]
+    int64_t ldc;
+    int M, N, K;
+    // grouped mode
+    const int32_t *offsets;      // [E+1]
+    const int32_t *tile_expert;  // [max_m_tiles]
+    const int32_t *tile_row;     // [max_m_tiles] first row of the tile
+    const int32_t *num_tiles;    // [1]
+    int max_m_tiles;             // host upper bound of *num_tiles (sizes the grid)
+};
+
+// Rows per M tile the grouped bf16 / fp32 GEMMs will use for a problem with `avg_rows` rows per
+// expert; the tile map must be built with the same value.
+int gemm_block_m(int dtype, int64_t n_rows, int E);
+
+// out_f32: C is fp32 (else elem); relu: max(.,0) before the store.
+int launch_gemm(int dtype, const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu,
+                int num_cus, hipStream_t s);
+
+// Tile map for the grouped GEMM from the device-side offsets (one block).
+int launch_tile_map(const int32_t *offsets, int E, int block_m, int32_t *tile_expert, int32_t *tile_row,
+                    int32_t *num_tiles, int max_m_tiles, hipStream_t s);
+
+// ---- routing -------------------------------------------------------------------------------------
+int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s);
+// block_hist: scratch of route_blocks(T)*E int32
+int route_blocks(int T);
+int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets,
+                 int32_t *dst_row, int32_t *src_tok, int32_t *block_hist, hipStream_t s);
+
+// ---- row movement --------------------------------------------------------------------------------
+int launch_dispatch(int dtype, const void *x, const int32_t *dst_row, int T, int D, int k, void *xp,
+                    hipStream_t s);
+int launch_combine(int dtype, const void *yp, const int32_t *dst_row, const float *w, int T, int D, int k,
+                   void *y, hipStream_t s);
+
+}  // namespace moe355

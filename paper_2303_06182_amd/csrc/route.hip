@@ -1,0 +1,339 @@
+// Routing kernels: softmax + top-k over the gate logits, per-expert counts with a prefix
+// scan, the stable permutation of the assignments, and the M-tile map of the grouped GEMM.
+//
+// Paper: top-1 / top-2 gating (Sec. 2.3); dynamic gating sorts the expert assignments and counts
+// the occurrences of each expert (Sec. 5.1).  The sort here is a counting sort: its result is the
+// stable argsort (ascending token inside each expert) and costs O(N) instead of O(N log N).
+// Nothing uses atomics on global memory, so the permutation is the same on every run.
+#include "moe_internal.h"
+
+namespace moe355 {
+
+static constexpr int kThreads = 256;
+static constexpr int kWave = 64;
+
+// ------------------------------------------------------------------------------------------------
+// softmax + top-k.  G lanes (a power of two <= 64) share one token; lane `sub` holds logits
+// sub, sub+G, sub+2G, ...  Each of the k rounds takes the largest remaining logit; equal logits
+// go to the lower expert index (inside a lane indices ascend with the register slot, across
+// lanes the butterfly compares (value, index)).
+// ------------------------------------------------------------------------------------------------
+template <int G, int V>
+__global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
+                                                        int renorm, int32_t *__restrict__ idx,
+                                                        float *__restrict__ w)
+{
+    constexpr int TOK_PER_BLOCK = kThreads / G;
+    const int sub = threadIdx.x % G;
+    const int t = blockIdx.x * TOK_PER_BLOCK + threadIdx.x / G;
+    const bool live = t < T;
+    const float NEG_INF = -__builtin_huge_valf();
+
+    float v[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const int e = sub + i * G;
+        v[i] = (live && e < E) ? logits[(int64_t)t * E + e] : NEG_INF;
+    }
+    uint32_t taken = 0;  // bit i: register slot i already selected
+#pragma unroll
+    for (int i = 0; i < V; ++i)
+        if (sub + i * G >= E) taken |= 1u << i;
+
+    float sel_v[MOE_MAX_K];
+    int sel_e[MOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+        sel_v[j] = NEG_INF;
+        sel_e[j] = 0;
+        if (j >= k) continue;  // uniform over the block
+        float bv = NEG_INF;
+        int be = 0x7fffffff;  // "none"
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const bool free_slot = !((taken >> i) & 1u);
+            if (free_slot && (be == 0x7fffffff || v[i] > bv)) {
+                bv = v[i];
+                be = sub + i * G;
+            }
+        }
+#pragma unroll
+        for (int off = G / 2; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, kWave);
+            const int oe = __shfl_xor(be, off, kWave);
+            const bool other_wins = (oe != 0x7fffffff) && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be));
+            if (other_wins) {
+                bv = ov;
+                be = oe;
+            }
+        }
+        // every lane of the group agrees for finite inputs; take lane 0's view so that the
+        // "taken" bookkeeping stays consistent whatever the inputs are
+        const int base = (threadIdx.x % kWave) - sub;
+        bv = __shfl(bv, base, kWave);
+        be = __shfl(be, base, kWave);
+        sel_v[j] = bv;
+        sel_e[j] = be;
+        if (be != 0x7fffffff && (be % G) == sub) taken |= 1u << (be / G);
+    }
+
+    // gate weights in fp32: exp(l - max) over the selected (renorm) or over all experts
+    const float m = sel_v[0];
+    float denom = 0.f;
+    if (renorm) {
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j)
+            if (j < k) denom += expf(sel_v[j] - m);
+    } else {
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+            if (sub + i * G < E) part += expf(v[i] - m);
+#pragma unroll
+        for (int off = G / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, kWave);
+        denom = part;
+    }
+    if (live && sub == 0) {
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j) {
+            if (j < k) {
+                idx[(int64_t)t * k + j] = sel_e[j];
+                w[(int64_t)t * k + j] = expf(sel_v[j] - m) / denom;
+            }
+        }
+    }
+}
+
+template <int G, int V>
+static int launch_topk_t(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w,
+                         hipStream_t s)
+{
+    const int tpb = kThreads / G;
+    ProfScope ps("topk", s);
+    hipLaunchKernelGGL((topk_kernel<G, V>), dim3(ceil_div(T, tpb)), dim3(kThreads), 0, s, logits, T, E, k, renorm,
+                       idx, w);
+    MOE_LAUNCH_CHECK("topk_kernel");
+    return MOE_OK;
+}
+
+int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s)
+{
+    if (T == 0) return MOE_OK;
+    if (E <= 4) return launch_topk_t<4, 1>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 8) return launch_topk_t<8, 1>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 16) return launch_topk_t<16, 1>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 32) return launch_topk_t<32, 1>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 64) return launch_topk_t<64, 1>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 128) return launch_topk_t<64, 2>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 256) return launch_topk_t<64, 4>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 512) return launch_topk_t<64, 8>(logits, T, E, k, renorm, idx, w, s);
+    return launch_topk_t<64, 16>(logits, T, E, k, renorm, idx, w, s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// counts / offsets / stable permutation.
+//   K1 route_hist : block b histograms its 256 tokens into LDS -> block_hist[b][e]
+//   K2 route_scan : per expert, exclusive prefix over the blocks (block_hist becomes the base of
+//                   block b inside expert e), counts[e], and offsets[] by a wave-shuffle scan
+//   K3 route_rank : block b ranks its tokens: ballot per expert inside a wave, LDS prefix over
+//                   the 4 waves, plus the block base and the expert offset
+// ------------------------------------------------------------------------------------------------
+int route_blocks(int T) { return T > 0 ? ceil_div(T, kThreads) : 1; }
+
+__device__ __forceinline__ int clamp_expert(int e, int E) { return e < 0 ? 0 : (e >= E ? E - 1 : e); }
+
+__global__ __launch_bounds__(kThreads) void route_hist_kernel(const int32_t *__restrict__ idx, int T, int E, int k,
+                                                              int32_t *__restrict__ block_hist)
+{
+    __shared__ int hist[MOE_MAX_E];
+    for (int e = threadIdx.x; e < E; e += kThreads) hist[e] = 0;
+    __syncthreads();
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    if (t < T) {
+        for (int j = 0; j < k; ++j) atomicAdd(&hist[clamp_expert(idx[(int64_t)t * k + j], E)], 1);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kThreads) block_hist[(int64_t)blockIdx.x * E + e] = hist[e];
+}
+
+// One block of 1024 threads.  Threads are laid out [segment][expert]: EP = E rounded up to a
+// power of two (>= 1), S = 1024 / EP segments, each covering a contiguous range of blocks.
+__global__ __launch_bounds__(1024) void route_scan_kernel(int32_t *__restrict__ block_hist, int nblk, int E, int EP,
+                                                          int total, int32_t *__restrict__ counts,
+                                                          int32_t *__restrict__ offsets)
+{
+    __shared__ int seg_sum[1024];
+    __shared__ int wave_tot[16];
+    const int S = 1024 / EP;
+    const int e = threadIdx.x % EP;
+    const int seg = threadIdx.x / EP;
+    const int per = ceil_div(nblk, S);
+    const int b0 = seg * per;
+    const int b1 = min(nblk, b0 + per);
+    int sum = 0;
+    if (e < E)
+        for (int b = b0; b < b1; ++b) sum += block_hist[(int64_t)b * E + e];
+    seg_sum[threadIdx.x] = sum;
+    __syncthreads();
+    int base = 0;
+    for (int s2 = 0; s2 < seg; ++s2) base += seg_sum[s2 * EP + e];
+    if (e < E) {
+        int run = base;
+        for (int b = b0; b < b1; ++b) {
+            const int v = block_hist[(int64_t)b * E + e];
+            block_hist[(int64_t)b * E + e] = run;
+            run += v;
+        }
+    }
+    // counts of expert `threadIdx.x` (threads 0..E-1), then exclusive scan over the experts
+    int cnt = 0;
+    if (threadIdx.x < E)
+        for (int s2 = 0; s2 < S; ++s2) cnt += seg_sum[s2 * EP + threadIdx.x];
+    int incl = cnt;
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    int wbase = 0;
+    for (int w2 = 0; w2 < wave; ++w2) wbase += wave_tot[w2];
+    if (threadIdx.x < E) {
+        counts[threadIdx.x] = cnt;
+        offsets[threadIdx.x] = wbase + incl - cnt;
+    }
+    if (threadIdx.x == 0) offsets[E] = total;
+}
+
+__global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__restrict__ idx, int T, int E, int k,
+                                                              const int32_t *__restrict__ offsets,
+                                                              const int32_t *__restrict__ block_base,
+                                                              int32_t *__restrict__ dst_row,
+                                                              int32_t *__restrict__ src_tok)
+{
+    constexpr int NW = kThreads / kWave;
+    __shared__ int wave_cnt[NW][MOE_MAX_E];
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    int ej[MOE_MAX_K];
+    int rank[MOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+        ej[j] = (t < T && j < k) ? clamp_expert(idx[(int64_t)t * k + j], E) : -1;
+        rank[j] = 0;
+    }
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+    for (int e = 0; e < E; ++e) {
+        int slot = -1;
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j)
+            if (ej[j] == e) slot = j;
+        const uint64_t mask = __ballot(slot >= 0);
+        if (slot >= 0) {
+            const int r = __popcll(mask & lt_mask);
+#pragma unroll
+            for (int j = 0; j < MOE_MAX_K; ++j)
+                if (j == slot) rank[j] = r;
+        }
+        if (lane == 0) wave_cnt[wave][e] = __popcll(mask);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kThreads) {
+        int run = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) {
+            const int c = wave_cnt[w2][e];
+            wave_cnt[w2][e] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    if (t < T) {
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j) {
+            if (j < k) {
+                const int e = ej[j];
+                const int r = offsets[e] + block_base[(int64_t)blockIdx.x * E + e] + wave_cnt[wave][e] + rank[j];
+                dst_row[(int64_t)t * k + j] = r;
+                src_tok[r] = t;
+            }
+        }
+    }
+}
+
+int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,
+                 int32_t *src_tok, int32_t *block_hist, hipStream_t s)
+{
+    const int nblk = route_blocks(T);
+    int EP = 1;
+    while (EP < E) EP <<= 1;
+    ProfScope ps("route", s);  // histogram + scan + rank together
+    hipLaunchKernelGGL(route_hist_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, block_hist);
+    MOE_LAUNCH_CHECK("route_hist_kernel");
+    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, nblk, E, EP, T * k, counts, offsets);
+    MOE_LAUNCH_CHECK("route_scan_kernel");
+    if (T > 0) {
+        hipLaunchKernelGGL(route_rank_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets, block_hist,
+                           dst_row, src_tok);
+        MOE_LAUNCH_CHECK("route_rank_kernel");
+    }
+    return MOE_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// M-tile map of the grouped GEMM: expert e owns ceil(count_e / BM) tiles; tile i of the flat list
+// starts at row tile_row[i] of expert tile_expert[i].  Experts with no rows own no tile, so their
+// weights are never touched.  One block of 1024 threads, thread e handles expert e, e + 1024, ...
+// (E <= 1024 here, so one expert per thread).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t *__restrict__ offsets, int E, int BM,
+                                                        int32_t *__restrict__ tile_expert,
+                                                        int32_t *__restrict__ tile_row,
+                                                        int32_t *__restrict__ num_tiles, int max_m_tiles)
+{
+    __shared__ int wave_tot[16];
+    const int e = threadIdx.x;
+    int row0 = 0, row1 = 0;
+    if (e < E) {
+        row0 = offsets[e];
+        row1 = offsets[e + 1];
+    }
+    const int nt = (row1 > row0) ? (row1 - row0 + BM - 1) / BM : 0;
+    int incl = nt;
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    int wbase = 0;
+    for (int w2 = 0; w2 < wave; ++w2) wbase += wave_tot[w2];
+    const int first = wbase + incl - nt;
+    for (int i = 0; i < nt; ++i) {
+        const int ti = first + i;
+        if (ti < max_m_tiles) {  // cannot fail when offsets are consistent with the host's bound
+            tile_expert[ti] = e;
+            tile_row[ti] = row0 + i * BM;
+        }
+    }
+    if (threadIdx.x == 1023) num_tiles[0] = min(first + nt, max_m_tiles);
+}
+
+int launch_tile_map(const int32_t *offsets, int E, int block_m, int32_t *tile_expert, int32_t *tile_row,
+                    int32_t *num_tiles, int max_m_tiles, hipStream_t s)
+{
+    ProfScope ps("tile_map", s);
+    hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(1024), 0, s, offsets, E, block_m, tile_expert, tile_row,
+                       num_tiles, max_m_tiles);
+    MOE_LAUNCH_CHECK("tile_map_kernel");
+    return MOE_OK;
+}
+
+}  // namespace moe355

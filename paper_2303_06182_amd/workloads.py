@@ -178,15 +178,17 @@ def redraw_rows(w: Workload, x: torch.Tensor, rows: torch.Tensor, attempt: int) 
 
 def clear_margins(w: Workload, x: torch.Tensor, margin_fn, delta: float = 2.0 ** -20,
                   max_attempts: int = 16) -> int:
-    """Redraw tokens until margin_fn(x)[t] >= delta for every token.  margin_fn is supplied
-    by the caller (it is the caller's business how a margin is computed); returns how many
-    token draws were replaced."""
+    """Redraw token rows until every token's decision margin is at least delta.
+    margin_fn(rows_of_x) -> one margin per given row; it is supplied by the caller (how a
+    margin is computed is the caller's business, this module only redraws).  Returns how
+    many token draws were replaced."""
+    rows = torch.arange(x.shape[0])
     total = 0
     for attempt in range(1, max_attempts + 1):
-        m = margin_fn(x)
-        bad = torch.nonzero(torch.as_tensor(m) < delta).flatten()
-        if bad.numel() == 0:
+        m = torch.as_tensor(margin_fn(x[rows.to(x.device)]))
+        rows = rows[(m < delta).cpu()]
+        if rows.numel() == 0:
             return total
-        total += int(bad.numel())
-        redraw_rows(w, x, bad, attempt)
+        total += int(rows.numel())
+        redraw_rows(w, x, rows, attempt)
     raise RuntimeError("margin guard did not converge")
