@@ -9,23 +9,31 @@
 // a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA blocks (v_mfma_f32_32x32x16_bf16).
 //
 // LDS layout: tile rows of 64 bf16 = 128 B = 8 chunks of 16 B; chunk c of row r is stored at
-// chunk position c ^ (r & 7), so the 8 rows a group of 8 lanes reads at the same K chunk fall
-// into 8 different bank groups (no conflict for ds_read_b128), and the 8 chunks of one row
-// written by 8 consecutive lanes do too.
+// chunk position c ^ ((r >> 1) & 7).  gfx950's LDS serves a 16-byte-per-lane read 16 consecutive
+// lanes (256 B, 64 banks) per clock: the 16 rows such a group reads at one K chunk are 8 even rows
+// (first half of the banks) and 8 odd rows (second half), and the swizzle gives each half 8
+// different chunk positions, so fragment reads are conflict free (measured: 4 clk per
+// ds_read_b128 against 6 clk with an (r & 7) swizzle); the 16 chunks two rows' writers store are
+// 256 contiguous bytes.
 //
-// Pipeline: double-buffered LDS, global loads of K-tile kt+1 are issued before the MFMAs of
-// K-tile kt and written to the other buffer after them; one barrier per K-tile.
+// Pipeline: double-buffered LDS; the loads of K-tile kt+1 go straight from global memory into the
+// other LDS stage (no register staging) and are issued before the MFMAs of K-tile kt; one barrier
+// per K-tile.
 //
 // Launch: 1-D grid.  Workgroups are handed to the 8 XCDs round-robin, each XCD has its own L2, so
 // the block id is first remapped to give every XCD a contiguous range of logical tiles; inside
 // the range tiles are ordered GM M-tiles at a time across all N-tiles, so tiles that run together
 // on an XCD share A rows and B (weight) rows.
+#include <stdlib.h>
+
 #include "moe_internal.h"
 
 namespace moe355 {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) void glb_void;
 
 static constexpr int BK = 64;
 static constexpr int GROUP_M = 4;
@@ -38,7 +46,7 @@ __device__ __forceinline__ uint16_t to_bf16(float f)
 }
 __device__ __forceinline__ float from_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED>
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
 {
     constexpr int THREADS = WM * WN * 64;
@@ -48,7 +56,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
     static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "tile rows must split evenly over threads");
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
     uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [2][BM*64]
     uint16_t *sB = sA + 2 * BM * BK;                        // [2][BN*64]
 
@@ -84,46 +92,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
     const int wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- global -> LDS copy assignment: chunk c = tid + i*THREADS; row = c >> 3, kc = c & 7 -----
-    const uint16_t *a_ptr[A_IT];
-    const uint16_t *b_ptr[B_IT];
-    int a_lds[A_IT], b_lds[B_IT];
-    const int kc = tid & 7;
-#pragma unroll
-    for (int i = 0; i < A_IT; ++i) {
-        const int r = (tid + i * THREADS) >> 3;
-        const int gr = min(row0 + r, row_end - 1);  // rows past the end repeat the last one (never stored)
-        a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
-        a_lds[i] = r * BK + ((kc ^ (r & 7)) << 3);
-    }
-#pragma unroll
-    for (int i = 0; i < B_IT; ++i) {
-        const int r = (tid + i * THREADS) >> 3;
-        const int gn = min(n0 + r, p.N - 1);
-        b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
-        b_lds[i] = r * BK + ((kc ^ (r & 7)) << 3);
-    }
-    const bool k_full = (K % BK) == 0;
-    const int KT = (K + BK - 1) / BK;
-
-    uint4 a_reg[A_IT], b_reg[B_IT];
-    auto load_global = [&](int kt) {
-        const int k0 = kt * BK;
-        const bool ok = k_full || (k0 + kc * 8 < K);
-#pragma unroll
-        for (int i = 0; i < A_IT; ++i)
-            a_reg[i] = ok ? *reinterpret_cast<const uint4 *>(a_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i)
-            b_reg[i] = ok ? *reinterpret_cast<const uint4 *>(b_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4 *>(sA + buf * BM * BK + a_lds[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4 *>(sB + buf * BN * BK + b_lds[i]) = b_reg[i];
-    };
-
     f32x16 acc[MI][NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
@@ -135,35 +103,129 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
     // fragment read offsets: row = (wave tile) + mi*32 + (lane & 31), K chunk = ks*2 + (lane >> 5)
     const int frag_row = lane & 31;
     const int frag_half = lane >> 5;
-    const int swz = lane & 7;  // == row & 7 for every row this lane reads
+    const int swz = (lane >> 1) & 7;  // == (row >> 1) & 7 for every row this lane reads
+    const int KT = (K + BK - 1) / BK;
 
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) load_global(kt + 1);
+    // MFMAs of one K tile out of LDS stage `cur`; the fragments of K-step ks+1 are fetched while
+    // the MFMAs of K-step ks run.
+    auto compute = [&](int cur) {
         const uint16_t *cA = sA + cur * BM * BK + (wm * WTM + frag_row) * BK;
         const uint16_t *cB = sB + cur * BN * BK + (wn * WTN + frag_row) * BK;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
+        bf16x8 af[2][MI], bfr[2][NI];
+        auto load_frags = [&](int ks, int set) {
             const int chunk = ((ks * 2 + frag_half) ^ swz) << 3;
-            bf16x8 af[MI], bfr[NI];
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                af[mi] = *reinterpret_cast<const bf16x8 *>(cA + mi * 32 * BK + chunk);
+                af[set][mi] = *reinterpret_cast<const bf16x8 *>(cA + mi * 32 * BK + chunk);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                bfr[ni] = *reinterpret_cast<const bf16x8 *>(cB + ni * 32 * BK + chunk);
+                bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(cB + ni * 32 * BK + chunk);
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) load_frags(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][mi], bfr[ks & 1][ni], acc[mi][ni],
+                                                                          0, 0, 0);
         }
-        if (kt + 1 < KT) store_lds(cur ^ 1);
+    };
+
+    if constexpr (KFULL) {
+        // ---- global -> LDS without registers (global_load_lds_dwordx4): one instruction moves 64
+        // lanes x 16 B = 1 KB = 8 tile rows straight into LDS, lane L landing at byte 16*L of the
+        // instruction's LDS base.  The base is fixed per instruction, so the swizzle is applied on
+        // the global side: the lane that lands in chunk slot (L & 7) of row r fetches K chunk
+        // (L & 7) ^ ((r >> 1) & 7).  Instruction i of wave w fills rows (w*IT + i)*8 .. +7.
+        // The loads of K tile kt+1 are issued before the MFMAs of K tile kt and are waited for
+        // (vmcnt) only at the barrier that ends the iteration.
+        const uint16_t *a_ptr[A_IT];
+        const uint16_t *b_ptr[B_IT];
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int r = (wave * A_IT + i) * 8 + (lane >> 3);
+            const int kc = (lane & 7) ^ ((r >> 1) & 7);
+            const int gr = min(row0 + r, row_end - 1);  // rows past the end repeat the last one (never stored)
+            a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            const int r = (wave * B_IT + i) * 8 + (lane >> 3);
+            const int kc = (lane & 7) ^ ((r >> 1) & 7);
+            const int gn = min(n0 + r, p.N - 1);
+            b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
+        }
+        auto issue = [&](int kt, int buf) {
+#pragma unroll
+            for (int i = 0; i < A_IT; ++i)
+                __builtin_amdgcn_global_load_lds((const glb_void *)(a_ptr[i] + kt * BK),
+                                                 (lds_void *)(sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK), 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < B_IT; ++i)
+                __builtin_amdgcn_global_load_lds((const glb_void *)(b_ptr[i] + kt * BK),
+                                                 (lds_void *)(sB + buf * BN * BK + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
+        };
+        issue(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < KT) issue(kt + 1, cur ^ 1);
+            compute(cur);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+    } else {
+        // ---- K not a multiple of the K tile: stage through registers so the tail can be zero filled.
+        // chunk c = tid + i*THREADS; row = c >> 3, kc = c & 7
+        const uint16_t *a_ptr[A_IT];
+        const uint16_t *b_ptr[B_IT];
+        int a_lds[A_IT], b_lds[B_IT];
+        const int kc = tid & 7;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int r = (tid + i * THREADS) >> 3;
+            const int gr = min(row0 + r, row_end - 1);
+            a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
+            a_lds[i] = r * BK + ((kc ^ ((r >> 1) & 7)) << 3);
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            const int r = (tid + i * THREADS) >> 3;
+            const int gn = min(n0 + r, p.N - 1);
+            b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
+            b_lds[i] = r * BK + ((kc ^ ((r >> 1) & 7)) << 3);
+        }
+        uint4 a_reg[A_IT], b_reg[B_IT];
+        auto load_global = [&](int kt) {
+            const int k0 = kt * BK;
+            const bool ok = k0 + kc * 8 < K;
+#pragma unroll
+            for (int i = 0; i < A_IT; ++i)
+                a_reg[i] = ok ? *reinterpret_cast<const uint4 *>(a_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < B_IT; ++i)
+                b_reg[i] = ok ? *reinterpret_cast<const uint4 *>(b_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
+        };
+        auto store_lds = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4 *>(sA + buf * BM * BK + a_lds[i]) = a_reg[i];
+#pragma unroll
+            for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4 *>(sB + buf * BN * BK + b_lds[i]) = b_reg[i];
+        };
+        load_global(0);
+        store_lds(0);
+        __syncthreads();
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < KT) load_global(kt + 1);
+            compute(cur);
+            if (kt + 1 < KT) store_lds(cur ^ 1);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: acc register r of a 32x32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
@@ -194,8 +256,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED>
-static int launch_one(const GemmParams &p, hipStream_t s)
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL>
+static int launch_k(const GemmParams &p, hipStream_t s)
 {
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
@@ -207,7 +269,7 @@ static int launch_one(const GemmParams &p, hipStream_t s)
         return MOE_ERR_UNSUPPORTED;
     }
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(uint16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED>;
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL>;
     if (smem > 48 * 1024) {
         static bool attr_set = false;  // per instantiation
         if (!attr_set) {
@@ -221,13 +283,55 @@ static int launch_one(const GemmParams &p, hipStream_t s)
     return MOE_OK;
 }
 
-int gemm_bf16_block_m(int64_t n_rows, int E)
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED>
+static int launch_one(const GemmParams &p, hipStream_t s)
 {
+    // K a multiple of the K tile: no per-load tail predicate in the main loop
+    return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true>(p, s)
+                           : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false>(p, s);
+}
+
+// Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves)
+//   1: 128x128, 4 waves   2: 64x128, 4 waves   3: 32x128, 4 waves
+//   4: 256x256, 4 waves   5: 256x256, 8 waves  6: 256x128, 4 waves   7: 128x256, 4 waves
+static int forced_variant()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("MOE355_GEMM_VARIANT");  // tuning override, 0 / unset = automatic
+        v = e ? atoi(e) : 0;
+        if (v < 0 || v > 7) v = 0;
+    }
+    return v;
+}
+
+static int variant_block_m(int v)
+{
+    switch (v) {
+    case 1: case 7: return 128;
+    case 2: return 64;
+    case 3: return 32;
+    default: return 256;
+    }
+}
+
+static int pick_variant(int64_t n_rows, int E)
+{
+    const int f = forced_variant();
+    if (f) return f;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
-    if (avg >= 512) return 128;
-    if (avg >= 96) return 128;
-    if (avg >= 48) return 64;
-    return 32;
+    if (avg >= 96) return 1;
+    if (avg >= 48) return 2;
+    return 3;
+}
+
+int gemm_bf16_block_m(int64_t n_rows, int E) { return variant_block_m(pick_variant(n_rows, E)); }
+
+template <int BM, int BN, int WM, int WN>
+static int launch_grouped(const GemmParams &p, bool relu, hipStream_t s)
+{
+    return relu ? launch_one<BM, BN, WM, WN, false, true, true>(p, s)
+                : launch_one<BM, BN, WM, WN, false, false, true>(p, s);
 }
 
 // Dispatch over the instantiated shapes.
@@ -247,18 +351,18 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
         set_error("grouped bf16 GEMM is only instantiated for bf16 output");
         return MOE_ERR_UNSUPPORTED;
     }
-    switch (block_m) {
-    case 128:
-        return relu ? launch_one<128, 128, 2, 2, false, true, true>(p, s)
-                    : launch_one<128, 128, 2, 2, false, false, true>(p, s);
-    case 64:
-        return relu ? launch_one<64, 128, 1, 4, false, true, true>(p, s)
-                    : launch_one<64, 128, 1, 4, false, false, true>(p, s);
-    case 32:
-        return relu ? launch_one<32, 128, 1, 4, false, true, true>(p, s)
-                    : launch_one<32, 128, 1, 4, false, false, true>(p, s);
+    int v = forced_variant();
+    if (!v || variant_block_m(v) != block_m) v = block_m == 128 ? 1 : block_m == 64 ? 2 : block_m == 32 ? 3 : 4;
+    switch (v) {
+    case 1: return launch_grouped<128, 128, 2, 2>(p, relu, s);
+    case 2: return launch_grouped<64, 128, 1, 4>(p, relu, s);
+    case 3: return launch_grouped<32, 128, 1, 4>(p, relu, s);
+    case 4: return launch_grouped<256, 256, 2, 2>(p, relu, s);
+    case 5: return launch_grouped<256, 256, 2, 4>(p, relu, s);
+    case 6: return launch_grouped<256, 128, 2, 2>(p, relu, s);
+    case 7: return launch_grouped<128, 256, 2, 2>(p, relu, s);
     default:
-        set_error("unsupported block_m %d", block_m);
+        set_error("unsupported GEMM variant %d", v);
         return MOE_ERR_UNSUPPORTED;
     }
 }
