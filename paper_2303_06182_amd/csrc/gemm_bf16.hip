@@ -6,24 +6,31 @@
 //
 // Both operands are K-contiguous, so every MFMA operand fragment (8 consecutive bf16 along K for
 // one row) is one 16-byte LDS read.  Tile: BM x BN x 64, WM x WN waves of 64 lanes, each wave owns
-// a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA blocks (v_mfma_f32_32x32x16_bf16).
+// a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA blocks (v_mfma_f32_32x32x16_bf16).  The weight
+// fragment is the MFMA's first operand and the activation fragment the second, so a lane ends up
+// with 4 CONSECUTIVE output columns of one output row per group of 4 accumulator registers and
+// stores them as one 8-byte (bf16) or 16-byte (fp32) access.
 //
 // LDS layout: tile rows of 64 bf16 = 128 B = 8 chunks of 16 B; chunk c of row r is stored at
 // chunk position c ^ ((r >> 1) & 7).  gfx950's LDS serves a 16-byte-per-lane read 16 consecutive
 // lanes (256 B, 64 banks) per clock: the 16 rows such a group reads at one K chunk are 8 even rows
 // (first half of the banks) and 8 odd rows (second half), and the swizzle gives each half 8
 // different chunk positions, so fragment reads are conflict free (measured: 4 clk per
-// ds_read_b128 against 6 clk with an (r & 7) swizzle); the 16 chunks two rows' writers store are
-// 256 contiguous bytes.
+// ds_read_b128 against 6 clk with an (r & 7) swizzle).
 //
-// Pipeline: double-buffered LDS; the loads of K-tile kt+1 go straight from global memory into the
-// other LDS stage (no register staging) and are issued before the MFMAs of K-tile kt; one barrier
-// per K-tile.
+// Pipeline: two LDS stages.  K tiles go straight from global memory into LDS
+// (global_load_lds_dwordx4, no register staging): the loads of K tile kt+1 are issued before the
+// MFMAs of K tile kt and waited for only at the barrier that ends the iteration.  Inside a K tile
+// the fragments of K-step ks+1 are read while the MFMAs of K-step ks issue (the instruction order
+// is pinned with sched_group_barrier, otherwise the compiler sinks the reads next to their use).
 //
-// Launch: 1-D grid.  Workgroups are handed to the 8 XCDs round-robin, each XCD has its own L2, so
-// the block id is first remapped to give every XCD a contiguous range of logical tiles; inside
-// the range tiles are ordered GM M-tiles at a time across all N-tiles, so tiles that run together
-// on an XCD share A rows and B (weight) rows.
+// Launch: PERSISTENT.  The grid is (CUs x resident blocks per CU); workgroups are handed to the 8
+// XCDs round-robin and each XCD has its own L2, so XCD x walks the contiguous range
+// [x*chunk, (x+1)*chunk) of the logical tile list, its blocks taking consecutive entries.  The
+// list orders tiles GROUP_M M-tiles at a time across all N-tiles, so the tiles an XCD works on
+// together share A rows and B (weight) rows.  The first K tile of a block's NEXT tile is loaded
+// during the last K iteration of the current one, so the pipeline never drains between tiles and
+// the epilogue's stores overlap the next tile's first iteration.
 #include <stdlib.h>
 
 #include "moe_internal.h"
@@ -38,16 +45,20 @@ typedef __attribute__((address_space(1))) void glb_void;
 static constexpr int BK = 64;
 static constexpr int GROUP_M = 4;
 
-__device__ __forceinline__ uint16_t to_bf16(float f)
+__device__ __forceinline__ uint32_t to_bf16(float f)
 {
     uint32_t u = __float_as_uint(f);
     u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return u >> 16;
 }
 __device__ __forceinline__ float from_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL>
-__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
+struct TileInfo {
+    int row0, row_end, expert, n0;
+};
+
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB>
+__global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams p)
 {
     constexpr int THREADS = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -60,66 +71,78 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
     uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [2][BM*64]
     uint16_t *sB = sA + 2 * BM * BK;                        // [2][BN*64]
 
-    // ---- which tile ----------------------------------------------------------------------------
-    const int n_tiles = (p.N + BN - 1) / BN;
-    const int G = gridDim.x;  // multiple of 8
-    const int bid = blockIdx.x;
-    const int lid = (bid & 7) * (G >> 3) + (bid >> 3);
-    const int per_group = GROUP_M * n_tiles;
-    const int grp = lid / per_group;
-    const int within = lid - grp * per_group;
-    const int mt = grp * GROUP_M + (within % GROUP_M);
-    const int nt = within / GROUP_M;
-    int row0, row_end, expert = 0;
-    if (GROUPED) {
-        if (mt >= p.num_tiles[0]) return;
-        expert = p.tile_expert[mt];
-        row0 = p.tile_row[mt];
-        row_end = p.offsets[expert + 1];
-    } else {
-        row0 = mt * BM;
-        row_end = p.M;
-        if (row0 >= row_end) return;
-    }
-    const int n0 = nt * BN;
-    const int K = p.K;
-
-    const uint16_t *Ag = static_cast<const uint16_t *>(p.A);
-    const uint16_t *Bg = static_cast<const uint16_t *>(p.B) + (int64_t)expert * p.strideB;
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
+    const int K = p.K;
+    const int KT = (K + BK - 1) / BK;
+
+    // ---- the block's sequence of tiles -----------------------------------------------------------
+    const int n_tiles = (p.N + BN - 1) / BN;
+    const int m_tiles = GROUPED ? p.num_tiles[0] : (p.M + BM - 1) / BM;
+    const int live = m_tiles * n_tiles;        // logical tiles
+    const int chunk = (live + 7) >> 3;         // per XCD
+    const int xcd = blockIdx.x & 7;
+    const int slots = gridDim.x >> 3;          // blocks per XCD (grid is a multiple of 8)
+    int seq = blockIdx.x >> 3;                 // position inside the XCD's chunk
+    auto seq_ok = [&](int sq) { return sq < chunk && xcd * chunk + sq < live; };
+    // logical tile -> (M tile, N tile): groups of GROUP_M M-tiles (the last group may be narrower),
+    // inside a group the M index runs fastest
+    auto tile_info = [&](int sq) {
+        const int lid = xcd * chunk + sq;
+        const int per_group = GROUP_M * n_tiles;
+        const int grp = lid / per_group;
+        const int within = lid - grp * per_group;
+        const int gsz = min(GROUP_M, m_tiles - grp * GROUP_M);
+        const int mt = grp * GROUP_M + within % gsz;
+        const int nt = within / gsz;
+        TileInfo t;
+        if (GROUPED) {
+            t.expert = p.tile_expert[mt];
+            t.row0 = p.tile_row[mt];
+            t.row_end = p.offsets[t.expert + 1];
+        } else {
+            t.expert = 0;
+            t.row0 = mt * BM;
+            t.row_end = p.M;
+        }
+        t.n0 = nt * BN;
+        return t;
+    };
+    if (!seq_ok(seq)) return;
+
+    const uint16_t *Ag = static_cast<const uint16_t *>(p.A);
+    const uint16_t *Bg0 = static_cast<const uint16_t *>(p.B);
 
     f32x16 acc[MI][NI];
+    auto zero_acc = [&]() {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    };
 
     // fragment read offsets: row = (wave tile) + mi*32 + (lane & 31), K chunk = ks*2 + (lane >> 5)
     const int frag_row = lane & 31;
     const int frag_half = lane >> 5;
     const int swz = (lane >> 1) & 7;  // == (row >> 1) & 7 for every row this lane reads
-    const int KT = (K + BK - 1) / BK;
 
-    // MFMAs of one K tile out of LDS stage `cur`; the fragments of K-step ks+1 are fetched while
-    // the MFMAs of K-step ks run.
+    // MFMAs of one K tile out of LDS stage `cur`.
     auto compute = [&](int cur) {
         const uint16_t *cA = sA + cur * BM * BK + (wm * WTM + frag_row) * BK;
         const uint16_t *cB = sB + cur * BN * BK + (wn * WTN + frag_row) * BK;
         bf16x8 af[2][MI], bfr[2][NI];
         auto load_frags = [&](int ks, int set) {
-            const int chunk = ((ks * 2 + frag_half) ^ swz) << 3;
+            const int chunkpos = ((ks * 2 + frag_half) ^ swz) << 3;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                af[set][mi] = *reinterpret_cast<const bf16x8 *>(cA + mi * 32 * BK + chunk);
+                af[set][mi] = *reinterpret_cast<const bf16x8 *>(cA + mi * 32 * BK + chunkpos);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(cB + ni * 32 * BK + chunk);
+                bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(cB + ni * 32 * BK + chunkpos);
         };
         load_frags(0, 0);
 #pragma unroll
@@ -129,35 +152,112 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][mi], bfr[ks & 1][ni], acc[mi][ni],
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][ni], af[ks & 1][mi], acc[mi][ni],
                                                                           0, 0, 0);
+            // issue order: one LDS read behind each of the first MFMAs, then the remaining MFMAs
+            if (ks + 1 < BK / 16) {
+                constexpr int NR = MI + NI, NM = MI * NI;
+#pragma unroll
+                for (int i = 0; i < (NR < NM ? NR : NM); ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                if (NR > NM) __builtin_amdgcn_sched_group_barrier(0x100, NR - NM, 0);
+                if (NM > NR) __builtin_amdgcn_sched_group_barrier(0x008, NM - NR, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
+    // ---- epilogue: acc[mi][ni] holds D[column][row]: lane -> row (lane & 31) of block mi, registers
+    // 4g..4g+3 -> columns 8g + 4*(lane >> 5) + 0..3 of block ni
+    auto epilogue = [&](const TileInfo &t) {
+        const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
+        if (bias) bias += (int64_t)t.expert * p.strideBias;
+        const bool vec_ok = !OUT_F32 || ((p.ldc & 3) == 0 && (p.N & 3) == 0);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int row = t.row0 + wm * WTM + mi * 32 + (lane & 31);
+            if (row >= t.row_end) continue;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = t.n0 + wn * WTN + ni * 32 + 8 * g + 4 * (lane >> 5);
+                    if (col >= p.N) continue;
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = acc[mi][ni][4 * g + i];
+                    if (bias) {
+                        if (col + 3 < p.N) {
+                            const uint2 bb = *reinterpret_cast<const uint2 *>(bias + col);
+                            v[0] += __uint_as_float(bb.x << 16);
+                            v[1] += __uint_as_float(bb.x & 0xffff0000u);
+                            v[2] += __uint_as_float(bb.y << 16);
+                            v[3] += __uint_as_float(bb.y & 0xffff0000u);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (col + i < p.N) v[i] += from_bf16(bias[col + i]);
+                        }
+                    }
+                    if (p.bias_f32) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (col + i < p.N) v[i] += p.bias_f32[col + i];
+                    }
+                    if (RELU) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.f ? v[i] : 0.f;
+                    }
+                    if (OUT_F32) {
+                        float *c = static_cast<float *>(p.C) + (int64_t)row * p.ldc + col;
+                        if (vec_ok) {
+                            *reinterpret_cast<float4 *>(c) = make_float4(v[0], v[1], v[2], v[3]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (col + i < p.N) c[i] = v[i];
+                        }
+                    } else {
+                        // bf16 output: N and ldc are multiples of 8 here, so the 4 columns exist
+                        uint2 o;
+                        o.x = to_bf16(v[0]) | (to_bf16(v[1]) << 16);
+                        o.y = to_bf16(v[2]) | (to_bf16(v[3]) << 16);
+                        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(p.C) + (int64_t)row * p.ldc + col) = o;
+                    }
+                }
+            }
+        }
+    };
+
+    TileInfo t = tile_info(seq);
+
     if constexpr (KFULL) {
-        // ---- global -> LDS without registers (global_load_lds_dwordx4): one instruction moves 64
-        // lanes x 16 B = 1 KB = 8 tile rows straight into LDS, lane L landing at byte 16*L of the
-        // instruction's LDS base.  The base is fixed per instruction, so the swizzle is applied on
-        // the global side: the lane that lands in chunk slot (L & 7) of row r fetches K chunk
-        // (L & 7) ^ ((r >> 1) & 7).  Instruction i of wave w fills rows (w*IT + i)*8 .. +7.
-        // The loads of K tile kt+1 are issued before the MFMAs of K tile kt and are waited for
-        // (vmcnt) only at the barrier that ends the iteration.
+        // ---- global -> LDS without registers: one global_load_lds_dwordx4 moves 64 lanes x 16 B =
+        // 1 KB = 8 tile rows into LDS, lane L landing at byte 16*L of the instruction's LDS base.
+        // The base is fixed per instruction, so the swizzle is applied on the global side: the lane
+        // that lands in chunk slot (L & 7) of row r fetches K chunk (L & 7) ^ ((r >> 1) & 7).
+        // Instruction i of wave w fills rows (w*IT + i)*8 .. +7.
         const uint16_t *a_ptr[A_IT];
         const uint16_t *b_ptr[B_IT];
+        auto set_ptrs = [&](const TileInfo &ti) {
+            const uint16_t *Bg = Bg0 + (int64_t)ti.expert * p.strideB;
 #pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
-            const int r = (wave * A_IT + i) * 8 + (lane >> 3);
-            const int kc = (lane & 7) ^ ((r >> 1) & 7);
-            const int gr = min(row0 + r, row_end - 1);  // rows past the end repeat the last one (never stored)
-            a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
-        }
+            for (int i = 0; i < A_IT; ++i) {
+                const int r = (wave * A_IT + i) * 8 + (lane >> 3);
+                const int kc = (lane & 7) ^ ((r >> 1) & 7);
+                const int gr = min(ti.row0 + r, ti.row_end - 1);  // rows past the end repeat the last one
+                a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
+            }
 #pragma unroll
-        for (int i = 0; i < B_IT; ++i) {
-            const int r = (wave * B_IT + i) * 8 + (lane >> 3);
-            const int kc = (lane & 7) ^ ((r >> 1) & 7);
-            const int gn = min(n0 + r, p.N - 1);
-            b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
-        }
+            for (int i = 0; i < B_IT; ++i) {
+                const int r = (wave * B_IT + i) * 8 + (lane >> 3);
+                const int kc = (lane & 7) ^ ((r >> 1) & 7);
+                const int gn = min(ti.n0 + r, p.N - 1);
+                b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
+            }
+        };
         auto issue = [&](int kt, int buf) {
 #pragma unroll
             for (int i = 0; i < A_IT; ++i)
@@ -168,139 +268,136 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(GemmParams p)
                 __builtin_amdgcn_global_load_lds((const glb_void *)(b_ptr[i] + kt * BK),
                                                  (lds_void *)(sB + buf * BN * BK + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
         };
+        set_ptrs(t);
         issue(0, 0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < KT) issue(kt + 1, cur ^ 1);
-            compute(cur);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+        int stage = 0;
+        while (true) {
+            zero_acc();
+            const int nseq = seq + slots;
+            const bool more = seq_ok(nseq);
+            TileInfo tn = t;
+            if (more) tn = tile_info(nseq);
+            for (int kt = 0; kt < KT; ++kt) {
+                if (kt + 1 < KT) {
+                    issue(kt + 1, stage ^ 1);
+                } else if (more) {  // the next tile's first K tile rides in the last iteration
+                    set_ptrs(tn);
+                    issue(0, stage ^ 1);
+                }
+                compute(stage);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                stage ^= 1;
+            }
+            epilogue(t);
+            if (!more) break;
+            seq = nseq;
+            t = tn;
         }
     } else {
         // ---- K not a multiple of the K tile: stage through registers so the tail can be zero filled.
         // chunk c = tid + i*THREADS; row = c >> 3, kc = c & 7
-        const uint16_t *a_ptr[A_IT];
-        const uint16_t *b_ptr[B_IT];
-        int a_lds[A_IT], b_lds[B_IT];
         const int kc = tid & 7;
+        while (true) {
+            const uint16_t *Bg = Bg0 + (int64_t)t.expert * p.strideB;
+            const uint16_t *a_ptr[A_IT];
+            const uint16_t *b_ptr[B_IT];
+            int a_lds[A_IT], b_lds[B_IT];
 #pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
-            const int r = (tid + i * THREADS) >> 3;
-            const int gr = min(row0 + r, row_end - 1);
-            a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
-            a_lds[i] = r * BK + ((kc ^ ((r >> 1) & 7)) << 3);
-        }
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i) {
-            const int r = (tid + i * THREADS) >> 3;
-            const int gn = min(n0 + r, p.N - 1);
-            b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
-            b_lds[i] = r * BK + ((kc ^ ((r >> 1) & 7)) << 3);
-        }
-        uint4 a_reg[A_IT], b_reg[B_IT];
-        auto load_global = [&](int kt) {
-            const int k0 = kt * BK;
-            const bool ok = k0 + kc * 8 < K;
-#pragma unroll
-            for (int i = 0; i < A_IT; ++i)
-                a_reg[i] = ok ? *reinterpret_cast<const uint4 *>(a_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < B_IT; ++i)
-                b_reg[i] = ok ? *reinterpret_cast<const uint4 *>(b_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
-        };
-        auto store_lds = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4 *>(sA + buf * BM * BK + a_lds[i]) = a_reg[i];
-#pragma unroll
-            for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4 *>(sB + buf * BN * BK + b_lds[i]) = b_reg[i];
-        };
-        load_global(0);
-        store_lds(0);
-        __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < KT) load_global(kt + 1);
-            compute(cur);
-            if (kt + 1 < KT) store_lds(cur ^ 1);
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue: acc register r of a 32x32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
-    const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
-    if (bias) bias += (int64_t)expert * p.strideBias;
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        const int col = n0 + wn * WTN + ni * 32 + (lane & 31);
-        if (col >= p.N) continue;
-        float badd = 0.f;
-        if (bias) badd += from_bf16(bias[col]);
-        if (p.bias_f32) badd += p.bias_f32[col];
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * WTM + mi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < row_end) {
-                    float v = acc[mi][ni][r] + badd;
-                    if (RELU) v = v > 0.f ? v : 0.f;
-                    if (OUT_F32)
-                        static_cast<float *>(p.C)[(int64_t)row * p.ldc + col] = v;
-                    else
-                        static_cast<uint16_t *>(p.C)[(int64_t)row * p.ldc + col] = to_bf16(v);
-                }
+            for (int i = 0; i < A_IT; ++i) {
+                const int r = (tid + i * THREADS) >> 3;
+                const int gr = min(t.row0 + r, t.row_end - 1);
+                a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
+                a_lds[i] = r * BK + ((kc ^ ((r >> 1) & 7)) << 3);
             }
+#pragma unroll
+            for (int i = 0; i < B_IT; ++i) {
+                const int r = (tid + i * THREADS) >> 3;
+                const int gn = min(t.n0 + r, p.N - 1);
+                b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
+                b_lds[i] = r * BK + ((kc ^ ((r >> 1) & 7)) << 3);
+            }
+            uint4 a_reg[A_IT], b_reg[B_IT];
+            auto load_global = [&](int kt) {
+                const int k0 = kt * BK;
+                const bool ok = k0 + kc * 8 < K;
+#pragma unroll
+                for (int i = 0; i < A_IT; ++i)
+                    a_reg[i] = ok ? *reinterpret_cast<const uint4 *>(a_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < B_IT; ++i)
+                    b_reg[i] = ok ? *reinterpret_cast<const uint4 *>(b_ptr[i] + k0) : make_uint4(0, 0, 0, 0);
+            };
+            auto store_lds = [&](int buf) {
+#pragma unroll
+                for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4 *>(sA + buf * BM * BK + a_lds[i]) = a_reg[i];
+#pragma unroll
+                for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4 *>(sB + buf * BN * BK + b_lds[i]) = b_reg[i];
+            };
+            zero_acc();
+            load_global(0);
+            store_lds(0);
+            __syncthreads();
+            for (int kt = 0; kt < KT; ++kt) {
+                const int cur = kt & 1;
+                if (kt + 1 < KT) load_global(kt + 1);
+                compute(cur);
+                if (kt + 1 < KT) store_lds(cur ^ 1);
+                __syncthreads();
+            }
+            epilogue(t);
+            seq += slots;
+            if (!seq_ok(seq)) break;
+            t = tile_info(seq);
         }
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL>
-static int launch_k(const GemmParams &p, hipStream_t s)
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB>
+static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
 {
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const int64_t logical = (int64_t)ceil_div(m_tiles, GROUP_M) * GROUP_M * n_tiles;
-    const int64_t grid = align_up(logical, 8);
-    if (grid > 0x7fffffff) {
-        set_error("GEMM grid too large");
-        return MOE_ERR_UNSUPPORTED;
-    }
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(uint16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL>;
-    if (smem > 48 * 1024) {
-        static bool attr_set = false;  // per instantiation
-        if (!attr_set) {
-            MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-            attr_set = true;
-        }
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB>;
+    static int blocks_per_cu = 0;  // per instantiation
+    if (blocks_per_cu == 0) {
+        MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        int occ = 0;
+        MOE_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, WM * WN * 64, smem));
+        blocks_per_cu = occ < 1 ? 1 : (occ > 4 ? 4 : occ);
     }
+    // persistent grid: every resident slot of the chip, but never more blocks than upper-bound tiles
+    int64_t grid = (int64_t)num_cus * blocks_per_cu;
+    const int64_t tiles = (int64_t)m_tiles * n_tiles;
+    if (grid > tiles) grid = tiles;
+    grid = align_up(grid, 8);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, s, p);
     MOE_LAUNCH_CHECK("gemm_bf16_kernel");
     return MOE_OK;
 }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED>
-static int launch_one(const GemmParams &p, hipStream_t s)
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, int MINB>
+static int launch_one(const GemmParams &p, int num_cus, hipStream_t s)
 {
-    // K a multiple of the K tile: no per-load tail predicate in the main loop
-    return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true>(p, s)
-                           : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false>(p, s);
+    // K a multiple of the K tile: direct-to-LDS main loop, no tail predicate
+    return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true, MINB>(p, num_cus, s)
+                           : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB>(p, num_cus, s);
 }
 
 // Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves)
-//   1: 128x128, 4 waves   2: 64x128, 4 waves   3: 32x128, 4 waves
-//   4: 256x256, 4 waves   5: 256x256, 8 waves  6: 256x128, 4 waves   7: 128x256, 4 waves
+//   1: 128x128, 4 waves   2: 64x128, 4 waves   3: 32x128, 4 waves   5: 256x256, 8 waves
 static int forced_variant()
 {
     static int v = -1;
     if (v < 0) {
         const char *e = getenv("MOE355_GEMM_VARIANT");  // tuning override, 0 / unset = automatic
         v = e ? atoi(e) : 0;
-        if (v < 0 || v > 7) v = 0;
+        if (v != 1 && v != 2 && v != 3 && v != 5) v = 0;
     }
     return v;
 }
@@ -308,7 +405,7 @@ static int forced_variant()
 static int variant_block_m(int v)
 {
     switch (v) {
-    case 1: case 7: return 128;
+    case 1: return 128;
     case 2: return 64;
     case 3: return 32;
     default: return 256;
@@ -320,6 +417,7 @@ static int pick_variant(int64_t n_rows, int E)
     const int f = forced_variant();
     if (f) return f;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
+    if (avg >= 192) return 5;
     if (avg >= 96) return 1;
     if (avg >= 48) return 2;
     return 3;
@@ -327,15 +425,16 @@ static int pick_variant(int64_t n_rows, int E)
 
 int gemm_bf16_block_m(int64_t n_rows, int E) { return variant_block_m(pick_variant(n_rows, E)); }
 
-template <int BM, int BN, int WM, int WN>
-static int launch_grouped(const GemmParams &p, bool relu, hipStream_t s)
+template <int BM, int BN, int WM, int WN, int MINB>
+static int launch_grouped(const GemmParams &p, bool relu, int num_cus, hipStream_t s)
 {
-    return relu ? launch_one<BM, BN, WM, WN, false, true, true>(p, s)
-                : launch_one<BM, BN, WM, WN, false, false, true>(p, s);
+    return relu ? launch_one<BM, BN, WM, WN, false, true, true, MINB>(p, num_cus, s)
+                : launch_one<BM, BN, WM, WN, false, false, true, MINB>(p, num_cus, s);
 }
 
 // Dispatch over the instantiated shapes.
-int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, hipStream_t s)
+int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
+                     hipStream_t s)
 {
     if (!grouped) {
         // gate: fp32 logits, N = E is small
@@ -343,26 +442,21 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
             set_error("plain bf16 GEMM is only instantiated for fp32 output without ReLU");
             return MOE_ERR_UNSUPPORTED;
         }
-        if (p.N <= 32) return launch_one<128, 32, 4, 1, true, false, false>(p, s);
-        if (p.N <= 64) return launch_one<128, 64, 2, 2, true, false, false>(p, s);
-        return launch_one<128, 128, 2, 2, true, false, false>(p, s);
+        if (p.N <= 32) return launch_one<128, 32, 4, 1, true, false, false, 2>(p, num_cus, s);
+        if (p.N <= 64) return launch_one<128, 64, 2, 2, true, false, false, 2>(p, num_cus, s);
+        return launch_one<128, 128, 2, 2, true, false, false, 2>(p, num_cus, s);
     }
     if (out_f32) {
         set_error("grouped bf16 GEMM is only instantiated for bf16 output");
         return MOE_ERR_UNSUPPORTED;
     }
-    int v = forced_variant();
-    if (!v || variant_block_m(v) != block_m) v = block_m == 128 ? 1 : block_m == 64 ? 2 : block_m == 32 ? 3 : 4;
-    switch (v) {
-    case 1: return launch_grouped<128, 128, 2, 2>(p, relu, s);
-    case 2: return launch_grouped<64, 128, 1, 4>(p, relu, s);
-    case 3: return launch_grouped<32, 128, 1, 4>(p, relu, s);
-    case 4: return launch_grouped<256, 256, 2, 2>(p, relu, s);
-    case 5: return launch_grouped<256, 256, 2, 4>(p, relu, s);
-    case 6: return launch_grouped<256, 128, 2, 2>(p, relu, s);
-    case 7: return launch_grouped<128, 256, 2, 2>(p, relu, s);
+    switch (block_m) {
+    case 256: return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
+    case 128: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
+    case 64: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
+    case 32: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
     default:
-        set_error("unsupported GEMM variant %d", v);
+        set_error("unsupported GEMM block_m %d", block_m);
         return MOE_ERR_UNSUPPORTED;
     }
 }

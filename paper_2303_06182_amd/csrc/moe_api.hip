@@ -55,7 +55,8 @@ ProfScope::~ProfScope()
     if (slot >= 0 && g_prof) (void)hipEventRecord(g_prof->stop[slot], stream);
 }
 
-int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, hipStream_t s);
+int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
+                     hipStream_t s);
 int gemm_bf16_block_m(int64_t n_rows, int E);
 int launch_gemm_f32(const GemmParams &p, bool grouped, int block_m, bool relu, hipStream_t s);
 
@@ -67,9 +68,8 @@ int gemm_block_m(int dtype, int64_t n_rows, int E)
 int launch_gemm(int dtype, const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
                 hipStream_t s)
 {
-    (void)num_cus;
     ProfScope ps(!grouped ? "gate_gemm" : (relu ? "expert_gemm1" : "expert_gemm2"), s);
-    if (dtype == MOE_DTYPE_BF16) return launch_gemm_bf16(p, grouped, block_m, out_f32, relu, s);
+    if (dtype == MOE_DTYPE_BF16) return launch_gemm_bf16(p, grouped, block_m, out_f32, relu, num_cus, s);
     return launch_gemm_f32(p, grouped, block_m, relu, s);  // fp32 storage: C is fp32 either way
 }
 
