@@ -146,6 +146,9 @@ def main():
     ap.add_argument("--config", default="lm")
     ap.add_argument("--also", default="skewed_large", help="comma list of further workloads reported under 'also'")
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the CPU oracle's FFN sample (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB read + 1 GiB write elementwise kernel three times (untimed): gives counter runs "
+                         "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -158,6 +161,16 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     binding.load_library()
+
+    if args.copy_calibration:
+        # an int32 "+1" over 1 GiB: reads 1 GiB, writes 1 GiB, in a kernel no other step of this run uses
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     main_res = run_config(args.config, args.steps, args.warmup, keep_host_copy=args.cpu_tokens > 0)
     also = {}
