@@ -65,7 +65,7 @@ extern "C" {
 
 /* Shape of the layer.  Supported: dtype in {F32, BF16}; 1 <= E <= MOE_MAX_E;
  * 1 <= k <= min(E, MOE_MAX_K); D and F positive multiples of 8; T_max >= 0 with
- * k*T_max < 2^31 / max(D,F) rows addressable in 64 bits (checked). */
+ * k*T_max < 2^30 (row indices are int32). */
 typedef struct moe_config {
     int32_t T_max;       /* largest T any call on this handle will be given */
     int32_t D;
@@ -194,6 +194,10 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
  *                       (the formulation the paper identifies as the inefficiency);
  *   MOE_STATIC_INDEXED: same rows, moved by index.
  * dropped_count (device int32, may be NULL) receives the number of dropped assignments.
+ * routing_out (may be NULL): logits, topk_idx, topk_w as in the dynamic call; counts[e] = assignments
+ * of expert e BEFORE dropping, offsets = their exclusive scan; dst_row[t,j] = e*capacity + row inside
+ * the expert, or -1 for a dropped assignment; src_tok is not written.
+ * EINSUM mode needs masks of (E*capacity) x T and T x (E*capacity) elements in the workspace.
  * Workspace: moe_static_workspace_bytes(). */
 int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias,
                              const void *w1, const void *w2, const void *b1, const void *b2,

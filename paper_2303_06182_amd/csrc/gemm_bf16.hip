@@ -438,10 +438,12 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
 {
     if (!grouped) {
         // gate: fp32 logits, N = E is small
-        if (!out_f32 || relu) {
-            set_error("plain bf16 GEMM is only instantiated for fp32 output without ReLU");
+        if (relu) {
+            set_error("plain bf16 GEMM is not instantiated with ReLU");
             return MOE_ERR_UNSUPPORTED;
         }
+        // bf16 output: the dense mask multiplications of the static-capacity baseline
+        if (!out_f32) return launch_one<256, 256, 2, 4, false, false, false, 1>(p, num_cus, s);
         if (p.N <= 32) return launch_one<128, 32, 4, 1, true, false, false, 2>(p, num_cus, s);
         if (p.N <= 64) return launch_one<128, 64, 2, 2, true, false, false, 2>(p, num_cus, s);
         return launch_one<128, 128, 2, 2, true, false, false, 2>(p, num_cus, s);

@@ -68,7 +68,7 @@ int gemm_block_m(int dtype, int64_t n_rows, int E)
 int launch_gemm(int dtype, const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
                 hipStream_t s)
 {
-    ProfScope ps(!grouped ? "gate_gemm" : (relu ? "expert_gemm1" : "expert_gemm2"), s);
+    ProfScope ps(p.name ? p.name : (!grouped ? "gate_gemm" : (relu ? "expert_gemm1" : "expert_gemm2")), s);
     if (dtype == MOE_DTYPE_BF16) return launch_gemm_bf16(p, grouped, block_m, out_f32, relu, num_cus, s);
     return launch_gemm_f32(p, grouped, block_m, relu, s);  // fp32 storage: C is fp32 either way
 }
@@ -224,17 +224,15 @@ static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const fl
     return launch_topk(logits, T, c.E, c.k, c.renormalize, idx, w, s);
 }
 
-static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
-                         const void *b1, const void *b2, int n_rows, void *yp, void *ws, hipStream_t s)
+// Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows, F] and the tile arrays are scratch.
+static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
+                          const void *b1, const void *b2, int64_t n_rows, void *yp, void *hbuf, int32_t *tile_expert,
+                          int32_t *tile_row, int32_t *num_tiles, hipStream_t s)
 {
     const moe_config_t &c = h->cfg;
     if (n_rows == 0) return MOE_OK;
-    const WsLayout L = ws_layout(c);
     const int bm = gemm_block_m(c.dtype, n_rows, c.E);
-    const int max_tiles = n_rows / bm + c.E + 1;
-    int32_t *tile_expert = at<int32_t>(ws, L.tile_expert);
-    int32_t *tile_row = at<int32_t>(ws, L.tile_row);
-    int32_t *num_tiles = at<int32_t>(ws, L.num_tiles);
+    const int max_tiles = (int)(n_rows / bm) + c.E + 1;
     int rc = launch_tile_map(offsets, c.E, bm, tile_expert, tile_row, num_tiles, max_tiles, s);
     if (rc != MOE_OK) return rc;
 
@@ -245,7 +243,7 @@ static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets
     p.tile_row = tile_row;
     p.num_tiles = num_tiles;
     p.max_m_tiles = max_tiles;
-    p.M = n_rows;
+    p.M = (int)n_rows;
     // H = relu(Xp * W1[e]^T + b1[e])
     p.A = xp;
     p.lda = c.D;
@@ -254,14 +252,14 @@ static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets
     p.strideB = (int64_t)c.F * c.D;
     p.bias = b1;
     p.strideBias = c.F;
-    p.C = at<void>(ws, L.h);
+    p.C = hbuf;
     p.ldc = c.F;
     p.N = c.F;
     p.K = c.D;
     rc = launch_gemm(c.dtype, p, true, bm, false, true, h->num_cus, s);
     if (rc != MOE_OK) return rc;
     // Yp = H * W2[e]^T + b2[e]
-    p.A = at<void>(ws, L.h);
+    p.A = hbuf;
     p.lda = c.F;
     p.B = w2;
     p.ldb = c.F;
@@ -273,6 +271,63 @@ static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets
     p.N = c.D;
     p.K = c.F;
     return launch_gemm(c.dtype, p, true, bm, false, false, h->num_cus, s);
+}
+
+static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
+                         const void *b1, const void *b2, int n_rows, void *yp, void *ws, hipStream_t s)
+{
+    const WsLayout L = ws_layout(h->cfg);
+    return run_expert_ffn(h, xp, offsets, w1, w2, b1, b2, n_rows, yp, at<void>(ws, L.h),
+                          at<int32_t>(ws, L.tile_expert), at<int32_t>(ws, L.tile_row), at<int32_t>(ws, L.num_tiles), s);
+}
+
+// ---- static-capacity baseline --------------------------------------------------------------------
+struct StaticLayout {
+    int64_t logits, topk_idx, topk_w, idx_t, counts_s, offsets_s, pos, src_s, block_hist, slot_row, row_tok;
+    int64_t offsets_static, tile_expert, tile_row, num_tiles, xd, hd, yd, xt, ydt, mask, cw, total;
+    int64_t ldt, ldk;  // padded leading dimensions (elements) of the T-long and E*cap-long K axes
+};
+
+static StaticLayout static_layout(const moe_config_t &c, int64_t T, int64_t cap, int mode)
+{
+    StaticLayout L;
+    memset(&L, 0, sizeof(L));
+    const int64_t N = T * c.k, E = c.E, es = elem_size(c.dtype), R = E * cap;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        const int64_t at = off;
+        off = align_up(off + (bytes > 0 ? bytes : 1), 256);
+        return at;
+    };
+    L.ldt = align_up(T, 64);
+    L.ldk = align_up(R, 64);
+    L.logits = take(T * E * 4);
+    L.topk_idx = take(N * 4);
+    L.topk_w = take(N * 4);
+    L.idx_t = take(N * 4);
+    L.counts_s = take(E * 4);
+    L.offsets_s = take((E + 1) * 4);
+    L.pos = take(N * 4);
+    L.src_s = take(N * 4);
+    L.block_hist = take((int64_t)route_blocks((int)N) * E * 4);
+    L.slot_row = take(N * 4);
+    L.row_tok = take(R * 4);
+    L.offsets_static = take((E + 1) * 4);
+    const int64_t max_tiles = R / kMinBlockM + E + 1;
+    L.tile_expert = take(max_tiles * 4);
+    L.tile_row = take(max_tiles * 4);
+    L.num_tiles = take(4);
+    L.xd = take(R * c.D * es);
+    L.hd = take(R * c.F * es);
+    L.yd = take(R * c.D * es);
+    if (mode == MOE_STATIC_EINSUM) {
+        L.xt = take((int64_t)c.D * L.ldt * es);
+        L.ydt = take((int64_t)c.D * L.ldk * es);
+        L.mask = take(R * L.ldt * es);
+        L.cw = take(T * L.ldk * es);
+    }
+    L.total = off;
+    return L;
 }
 
 }  // namespace moe355
@@ -522,6 +577,152 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
     rc = do_expert_ffn(h, xp, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
     if (rc != MOE_OK) return rc;
     return launch_combine(c.dtype, yp, dst_row, w, T, c.D, c.k, y, s);
+}
+
+int64_t moe_static_workspace_bytes(const moe_handle_t *h, int32_t T, int32_t capacity, int32_t mode)
+{
+    g_err[0] = 0;
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (T < 0 || T > h->cfg.T_max || capacity < 1 || (int64_t)capacity * h->cfg.E > 0x3fffffff) {
+        set_error("T = %d or capacity = %d out of range", T, capacity);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (mode != MOE_STATIC_EINSUM && mode != MOE_STATIC_INDEXED) {
+        set_error("unknown static mode %d", mode);
+        return MOE_ERR_INVALID_ARG;
+    }
+    return static_layout(h->cfg, T, capacity, mode).total;
+}
+
+int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1,
+                             const void *w2, const void *b1, const void *b2, int32_t T, int32_t capacity, int32_t mode,
+                             void *y, int32_t *dropped_count, const moe_routing_t *routing_out, void *workspace,
+                             int64_t workspace_bytes, void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    int rc = check_handle_T(h, T);
+    if (rc != MOE_OK) return rc;
+    const moe_config_t &c = h->cfg;
+    if (capacity < 1 || (int64_t)capacity * c.E > 0x3fffffff) {
+        set_error("capacity = %d out of range", capacity);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (mode != MOE_STATIC_EINSUM && mode != MOE_STATIC_INDEXED) {
+        set_error("unknown static mode %d", mode);
+        return MOE_ERR_INVALID_ARG;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (bad_ptr(dropped_count, "dropped_count", true)) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return dropped_count ? launch_fill_u32(dropped_count, 1, 0, s) : MOE_OK;
+    if (bad_ptr(x, "x") || bad_ptr(wg, "wg") || bad_ptr(gate_bias, "gate_bias", true) || bad_ptr(w1, "w1") ||
+        bad_ptr(w2, "w2") || bad_ptr(b1, "b1", true) || bad_ptr(b2, "b2", true) || bad_ptr(y, "y"))
+        return MOE_ERR_INVALID_ARG;
+    moe_routing_t r;
+    memset(&r, 0, sizeof(r));
+    if (routing_out) r = *routing_out;
+    if (bad_ptr(r.logits, "routing_out.logits", true) || bad_ptr(r.topk_idx, "routing_out.topk_idx", true) ||
+        bad_ptr(r.topk_w, "routing_out.topk_w", true) || bad_ptr(r.counts, "routing_out.counts", true) ||
+        bad_ptr(r.offsets, "routing_out.offsets", true) || bad_ptr(r.dst_row, "routing_out.dst_row", true))
+        return MOE_ERR_INVALID_ARG;
+    const StaticLayout L = static_layout(c, T, capacity, mode);
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0) {
+        set_error("workspace is NULL or not 256-byte aligned");
+        return MOE_ERR_WORKSPACE;
+    }
+    if (workspace_bytes < L.total) {
+        set_error("workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)L.total);
+        return MOE_ERR_WORKSPACE;
+    }
+    void *ws = workspace;
+    const int64_t R = (int64_t)c.E * capacity;
+    float *logits = r.logits ? r.logits : at<float>(ws, L.logits);
+    int32_t *idx = r.topk_idx ? r.topk_idx : at<int32_t>(ws, L.topk_idx);
+    float *w = r.topk_w ? r.topk_w : at<float>(ws, L.topk_w);
+    int32_t *counts_s = r.counts ? r.counts : at<int32_t>(ws, L.counts_s);
+    int32_t *offsets_s = r.offsets ? r.offsets : at<int32_t>(ws, L.offsets_s);
+    int32_t *slot_row = r.dst_row ? r.dst_row : at<int32_t>(ws, L.slot_row);
+    int32_t *dropped = dropped_count ? dropped_count : at<int32_t>(ws, L.num_tiles) + 1;  // spare word of the slot
+    int32_t *idx_t = at<int32_t>(ws, L.idx_t);
+    int32_t *pos = at<int32_t>(ws, L.pos);
+    int32_t *offsets_static = at<int32_t>(ws, L.offsets_static);
+    void *xd = at<void>(ws, L.xd);
+    void *yd = at<void>(ws, L.yd);
+
+    rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s);
+    if (rc != MOE_OK) return rc;
+    // slot of every assignment = its rank inside its expert in slot-major order
+    rc = launch_transpose_idx(idx, T, c.k, idx_t, dropped, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_route(idx_t, T * c.k, c.E, 1, counts_s, offsets_s, pos, at<int32_t>(ws, L.src_s),
+                      at<int32_t>(ws, L.block_hist), s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_static_rows(idx_t, pos, offsets_s, T, c.k, c.E, capacity, slot_row, dropped, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_static_offsets(offsets_static, c.E, capacity, s);
+    if (rc != MOE_OK) return rc;
+
+    GemmParams p;
+    if (mode == MOE_STATIC_INDEXED) {
+        int32_t *row_tok = at<int32_t>(ws, L.row_tok);
+        rc = launch_fill_u32(row_tok, R, 0xffffffffu, s);
+        if (rc != MOE_OK) return rc;
+        rc = launch_row_tokens(slot_row, T, c.k, row_tok, s);
+        if (rc != MOE_OK) return rc;
+        rc = launch_padded_gather(c.dtype, x, row_tok, R, c.D, xd, s);
+        if (rc != MOE_OK) return rc;
+    } else {
+        // dispatch = one-hot mask [E*cap, T] times x: Xd[r,:] = sum_t mask[r,t] * x[t,:]
+        const int64_t es = elem_size(c.dtype);
+        void *mask = at<void>(ws, L.mask);
+        void *cw = at<void>(ws, L.cw);
+        void *xt = at<void>(ws, L.xt);
+        rc = launch_fill_u32(mask, R * L.ldt * es / 4, 0, s);
+        if (rc != MOE_OK) return rc;
+        rc = launch_fill_u32(cw, (int64_t)T * L.ldk * es / 4, 0, s);
+        if (rc != MOE_OK) return rc;
+        rc = launch_static_masks(c.dtype, slot_row, w, T, c.k, mask, L.ldt, cw, L.ldk, s);
+        if (rc != MOE_OK) return rc;
+        rc = launch_transpose_pad(c.dtype, x, T, c.D, xt, L.ldt, s);
+        if (rc != MOE_OK) return rc;
+        memset(&p, 0, sizeof(p));
+        p.name = "static_dispatch_einsum";
+        p.A = mask;
+        p.lda = L.ldt;
+        p.B = xt;
+        p.ldb = L.ldt;
+        p.C = xd;
+        p.ldc = c.D;
+        p.M = (int)R;
+        p.N = c.D;
+        p.K = (int)L.ldt;
+        rc = launch_gemm(c.dtype, p, false, 0, c.dtype == MOE_DTYPE_F32, false, h->num_cus, s);
+        if (rc != MOE_OK) return rc;
+    }
+    // every expert processes all of its `capacity` rows, zero rows included
+    rc = run_expert_ffn(h, xd, offsets_static, w1, w2, b1, b2, R, yd, at<void>(ws, L.hd),
+                        at<int32_t>(ws, L.tile_expert), at<int32_t>(ws, L.tile_row), at<int32_t>(ws, L.num_tiles), s);
+    if (rc != MOE_OK) return rc;
+    if (mode == MOE_STATIC_INDEXED) return launch_combine(c.dtype, yd, slot_row, w, T, c.D, c.k, y, s);
+    // combine = weight mask [T, E*cap] times the expert outputs
+    void *ydt = at<void>(ws, L.ydt);
+    rc = launch_transpose_pad(c.dtype, yd, R, c.D, ydt, L.ldk, s);
+    if (rc != MOE_OK) return rc;
+    memset(&p, 0, sizeof(p));
+    p.name = "static_combine_einsum";
+    p.A = at<void>(ws, L.cw);
+    p.lda = L.ldk;
+    p.B = ydt;
+    p.ldb = L.ldk;
+    p.C = y;
+    p.ldc = c.D;
+    p.M = T;
+    p.N = c.D;
+    p.K = (int)L.ldk;
+    return launch_gemm(c.dtype, p, false, 0, c.dtype == MOE_DTYPE_F32, false, h->num_cus, s);
 }
 
 }  // extern "C"

@@ -18,6 +18,31 @@ struct Profiler {
     hipEvent_t stop[kMax];
     int created = 0;  // events [0, created) exist
 };
+
+// ---- static-capacity baseline (static_baseline.hip) ---------------------------------------------
+// idx [T,k] -> idx_t [k*T] (slot-major: all first choices, then all second choices, ...); also
+// clears dropped[0].
+int launch_transpose_idx(const int32_t *idx, int T, int k, int32_t *idx_t, int32_t *dropped, hipStream_t s);
+// pos [k*T] = offsets_s[e] + rank of the assignment inside expert e in slot-major order (from the
+// routing kernels run on idx_t).  slot_row[t,j] = e*capacity + slot, or -1 when slot >= capacity;
+// dropped[0] += number of -1.
+int launch_static_rows(const int32_t *idx_t, const int32_t *pos, const int32_t *offsets_s, int T, int k, int E,
+                       int capacity, int32_t *slot_row, int32_t *dropped, hipStream_t s);
+int launch_fill_u32(void *dst, int64_t n_words, uint32_t value, hipStream_t s);
+// row_tok[slot_row[t,j]] = t for kept assignments (row_tok pre-filled with -1)
+int launch_row_tokens(const int32_t *slot_row, int T, int k, int32_t *row_tok, hipStream_t s);
+// xd[r,:] = row_tok[r] >= 0 ? x[row_tok[r],:] : 0     (rows = E*capacity)
+int launch_padded_gather(int dtype, const void *x, const int32_t *row_tok, int64_t rows, int D, void *xd,
+                         hipStream_t s);
+// offsets_static[e] = e*capacity, e = 0..E
+int launch_static_offsets(int32_t *offsets_static, int E, int capacity, hipStream_t s);
+// out [C, ldo] = in[R, C]^T, columns R..ldo-1 zero     (element size 2 or 4 bytes)
+int launch_transpose_pad(int dtype, const void *in, int64_t R, int64_t C, void *out, int64_t ldo, hipStream_t s);
+// one-hot dispatch mask: mask[slot_row[t,j], t] = 1 (elem), ld = ldm;  combine weights:
+// cw[t, slot_row[t,j]] = w[t,j] (elem), ld = ldc.  Both pre-zeroed.
+int launch_static_masks(int dtype, const int32_t *slot_row, const float *w, int T, int k, void *mask, int64_t ldm,
+                        void *cw, int64_t ldc, hipStream_t s);
+
 }  // namespace moe355
 
 struct moe_handle {
@@ -81,6 +106,7 @@ struct GemmParams {
     const int32_t *tile_row;     // [max_m_tiles] first row of the tile
     const int32_t *num_tiles;    // [1]
     int max_m_tiles;             // host upper bound of *num_tiles (sizes the grid)
+    const char *name;            // host only: label of the launch for the event profiler (may be NULL)
 };
 
 // Rows per M tile the grouped bf16 / fp32 GEMMs will use for a problem with `avg_rows` rows per

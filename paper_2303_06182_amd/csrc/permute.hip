@@ -73,6 +73,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const uint4 *__restri
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
         for (int j = 0; j < k; ++j) {
             const int64_t r = dst_row[t * k + j];
+            if (r < 0) continue;  // an assignment dropped by a static capacity contributes nothing
             const float g = w[t * k + j];
             const uint4 q = yp[r * vpr + c];
             if (BF16) {
