@@ -114,6 +114,48 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
     return res
 
 
+def run_static(name, cfs, steps=3):
+    """The static-capacity baseline on the same workload: every expert owns cf * k*T/E rows,
+    overflow is dropped, unused rows are zero and still computed.  Both the index-moved and the
+    one-hot-mask ("einsum") forms."""
+    import torch
+    from paper_2303_06182_amd import binding, workloads as wl
+
+    w = wl.CONFIGS[name]
+    inp = wl.make_inputs(w, device="cuda")
+    layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
+    y = torch.empty((w.T, w.D), dtype=w.torch_dtype, device="cuda")
+    out = {}
+    for cf in cfs:
+        cap = binding.moe_capacity(w.T, w.E, w.k, cf, binding.MOE_CAPACITY_SHARE)
+        for mode, mname in ((binding.MOE_STATIC_INDEXED, "indexed"), (binding.MOE_STATIC_EINSUM, "einsum")):
+            nbytes = layer.moe_static_workspace_bytes(w.T, cap, mode)
+            free, _ = torch.cuda.mem_get_info()
+            if nbytes > free - (8 << 30):
+                out["cf%.1f_%s" % (cf, mname)] = dict(skipped="workspace of %d bytes does not fit" % nbytes)
+                continue
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+            def step():
+                return layer.moe_layer_forward_static(inp["x"], inp["wg"], inp["w1"], inp["w2"], cap, mode,
+                                                      inp["gate_bias"], y=y, workspace=ws)
+            _, dropped = step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            out["cf%.1f_%s" % (cf, mname)] = dict(
+                capacity_rows=cap, padded_rows=cap * w.E, needed_rows=w.k * w.T, dropped_assignments=int(dropped[0]),
+                ms_per_step=ms, tokens_per_s=w.T / (ms * 1e-3), workspace_bytes=nbytes)
+            del ws
+            torch.cuda.empty_cache()
+    del layer, inp, y
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(name, inp, budget_tokens):
     """The CPU oracle as it stands, timed on the host cores on a bounded sample of the same
     workload: the gate, top-k and routing for every token, the expert FFN and combine for
@@ -146,6 +188,7 @@ def main():
     ap.add_argument("--config", default="lm")
     ap.add_argument("--also", default="skewed_large", help="comma list of further workloads reported under 'also'")
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the CPU oracle's FFN sample (0 = skip)")
+    ap.add_argument("--no-static", action="store_true", help="skip the static-capacity baseline runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write elementwise kernel three times (untimed): gives counter runs "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) a kernel of known traffic to scale by")
@@ -180,6 +223,11 @@ def main():
                           kernels={k: dict(avg_ms=v["avg_ms"], bound=v["bound"], frac=v["frac"])
                                    for k, v in r["kernels"].items()},
                           max_expert_share=r["max_expert_share"])
+    static = {}
+    if not args.no_static:
+        static[args.config] = run_static(args.config, [1.0, 2.0])
+        for name in also:
+            static[name] = run_static(name, [1.0, 2.0])
     cpu = cpu_baseline(args.config, main_res["host"], args.cpu_tokens) if args.cpu_tokens > 0 else None
 
     dom = dict(main_res["dominant"])
@@ -204,6 +252,7 @@ def main():
         "kernels": {k: dict(avg_ms=v["avg_ms"], bound=v["bound"], achieved=v["achieved"], unit=v["unit"],
                             frac=v["frac"]) for k, v in main_res["kernels"].items()},
         "also": also,
+        "static_baseline": static,
         "paper_context": "paper reports only relative whole-model speedups of dynamic over static gating on "
                          "8xV100 nodes (LM 6.21-11.23x, MT encoder 5.75-10.98x, MT decoder 2.58-5.71x); "
                          "no absolute number exists for this metric",
