@@ -18,9 +18,10 @@
 // different chunk positions, so fragment reads are conflict free (measured: 4 clk per
 // ds_read_b128 against 6 clk with an (r & 7) swizzle).
 //
-// Pipeline: two LDS stages.  K tiles go straight from global memory into LDS
-// (global_load_lds_dwordx4, no register staging): the loads of K tile kt+1 are issued before the
-// MFMAs of K tile kt and waited for only at the barrier that ends the iteration.  Inside a K tile
+// Pipeline: STAGES LDS stages (2 for the big tiles, more for the small, latency-bound ones).  K
+// tiles go straight from global memory into LDS (global_load_lds_dwordx4, no register staging):
+// the loads run STAGES-1 K tiles ahead of the MFMAs and are waited for (vmcnt) only at the barrier
+// that ends an iteration.  Inside a K tile
 // the fragments of K-step ks+1 are read while the MFMAs of K-step ks issue (the instruction order
 // is pinned with sched_group_barrier, otherwise the compiler sinks the reads next to their use).
 //
@@ -28,9 +29,9 @@
 // XCDs round-robin and each XCD has its own L2, so XCD x walks the contiguous range
 // [x*chunk, (x+1)*chunk) of the logical tile list, its blocks taking consecutive entries.  The
 // list orders tiles GROUP_M M-tiles at a time across all N-tiles, so the tiles an XCD works on
-// together share A rows and B (weight) rows.  The first K tile of a block's NEXT tile is loaded
-// during the last K iteration of the current one, so the pipeline never drains between tiles and
-// the epilogue's stores overlap the next tile's first iteration.
+// together share A rows and B (weight) rows.  The load cursor walks the block's whole sequence of (tile, K tile)
+// pairs, so the first K tiles of the NEXT tile are loaded during the last iterations of the current
+// one: the pipeline never drains between tiles and the epilogue's stores overlap the next tile.
 #include <stdlib.h>
 
 #include "moe_internal.h"
@@ -57,7 +58,7 @@ struct TileInfo {
     int row0, row_end, expert, n0;
 };
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB>
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES>
 __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams p)
 {
     constexpr int THREADS = WM * WN * 64;
@@ -68,8 +69,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "tile rows must split evenly over threads");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
-    uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [2][BM*64]
-    uint16_t *sB = sA + 2 * BM * BK;                        // [2][BN*64]
+    uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [STAGES][BM*64]
+    uint16_t *sB = sA + STAGES * BM * BK;                   // [STAGES][BN*64]
+    static_assert(STAGES >= 2, "at least two LDS stages");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -268,34 +270,64 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 __builtin_amdgcn_global_load_lds((const glb_void *)(b_ptr[i] + kt * BK),
                                                  (lds_void *)(sB + buf * BN * BK + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
         };
+        // The loads run STAGES-1 K tiles ahead of the MFMAs along the block's whole sequence of
+        // (tile, K tile) pairs, so the pipeline never drains between tiles and an epilogue's stores
+        // overlap the next tile's first iterations.  Every call issues the same number of loads
+        // (past the end of the sequence it re-reads the last K tile into a stage nobody will use),
+        // which keeps the vmcnt arithmetic fixed: "at most (STAGES-2) stages' loads outstanding"
+        // means the K tile needed next has landed.
+        // The barrier between iterations is the bare s_barrier: __syncthreads() would add a full
+        // vmcnt(0) wait (it fences the outstanding LDS-bound loads), which serialises the stages.
+        // What the barrier must order is covered explicitly: (1) this wave's own global->LDS loads
+        // of the stage read next have landed -- the s_waitcnt vmcnt just before it; (2) this
+        // wave's LDS reads of the stage overwritten next have returned -- every fragment read is
+        // consumed by an MFMA issued before the barrier, and an MFMA does not issue before its
+        // operands arrived.
+        auto stage_barrier = [&]() {
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        constexpr int LPS = A_IT + B_IT;             // load instructions per wave per stage
+        constexpr int WAITN = (STAGES - 2) * LPS;
+        int l_seq = seq, l_kt = 0, l_stage = 0;
+        bool l_more = true;
         set_ptrs(t);
-        issue(0, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        auto issue_next = [&]() {
+            issue(l_kt, l_stage);
+            l_stage = (l_stage + 1 == STAGES) ? 0 : l_stage + 1;
+            if (l_more && ++l_kt == KT) {
+                if (seq_ok(l_seq + slots)) {
+                    l_seq += slots;
+                    l_kt = 0;
+                    set_ptrs(tile_info(l_seq));
+                } else {
+                    l_more = false;
+                    l_kt = KT - 1;
+                }
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < STAGES - 1; ++i) issue_next();
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WAITN) : "memory");
+        stage_barrier();
         int stage = 0;
         while (true) {
             zero_acc();
-            const int nseq = seq + slots;
-            const bool more = seq_ok(nseq);
-            TileInfo tn = t;
-            if (more) tn = tile_info(nseq);
             for (int kt = 0; kt < KT; ++kt) {
-                if (kt + 1 < KT) {
-                    issue(kt + 1, stage ^ 1);
-                } else if (more) {  // the next tile's first K tile rides in the last iteration
-                    set_ptrs(tn);
-                    issue(0, stage ^ 1);
-                }
+                issue_next();  // into the stage the previous iteration computed from
                 compute(stage);
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-                stage ^= 1;
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WAITN) : "memory");
+                stage_barrier();
+                stage = (stage + 1 == STAGES) ? 0 : stage + 1;
             }
             epilogue(t);
-            if (!more) break;
-            seq = nseq;
-            t = tn;
+            seq += slots;
+            if (!seq_ok(seq)) break;
+            t = tile_info(seq);
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no LDS write may outlive the block
     } else {
         // ---- K not a multiple of the K tile: stage through registers so the tail can be zero filled.
         // chunk c = tid + i*THREADS; row = c >> 3, kc = c & 7
@@ -355,21 +387,21 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB>
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES>
 static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
 {
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(uint16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB>;
+    const size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES>;
     static int blocks_per_cu = 0;  // per instantiation
     if (blocks_per_cu == 0) {
         MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         int occ = 0;
         MOE_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, WM * WN * 64, smem));
-        blocks_per_cu = occ < 1 ? 1 : (occ > 4 ? 4 : occ);
+        blocks_per_cu = occ < 1 ? 1 : (occ > 8 ? 8 : occ);
     }
     // persistent grid: every resident slot of the chip, but never more blocks than upper-bound tiles
     int64_t grid = (int64_t)num_cus * blocks_per_cu;
@@ -381,12 +413,13 @@ static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
     return MOE_OK;
 }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, int MINB>
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, int MINB, int STAGES = 2>
 static int launch_one(const GemmParams &p, int num_cus, hipStream_t s)
 {
-    // K a multiple of the K tile: direct-to-LDS main loop, no tail predicate
-    return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true, MINB>(p, num_cus, s)
-                           : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB>(p, num_cus, s);
+    // K a multiple of the K tile: direct-to-LDS main loop, no tail predicate; the register-staged
+    // fallback always uses two stages
+    return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true, MINB, STAGES>(p, num_cus, s)
+                           : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB, 2>(p, num_cus, s);
 }
 
 // Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves)
@@ -425,11 +458,11 @@ static int pick_variant(int64_t n_rows, int E)
 
 int gemm_bf16_block_m(int64_t n_rows, int E) { return variant_block_m(pick_variant(n_rows, E)); }
 
-template <int BM, int BN, int WM, int WN, int MINB>
+template <int BM, int BN, int WM, int WN, int MINB, int STAGES = 2>
 static int launch_grouped(const GemmParams &p, bool relu, int num_cus, hipStream_t s)
 {
-    return relu ? launch_one<BM, BN, WM, WN, false, true, true, MINB>(p, num_cus, s)
-                : launch_one<BM, BN, WM, WN, false, false, true, MINB>(p, num_cus, s);
+    return relu ? launch_one<BM, BN, WM, WN, false, true, true, MINB, STAGES>(p, num_cus, s)
+                : launch_one<BM, BN, WM, WN, false, false, true, MINB, STAGES>(p, num_cus, s);
 }
 
 // Dispatch over the instantiated shapes.
@@ -444,9 +477,18 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
         }
         // bf16 output: the dense mask multiplications of the static-capacity baseline
         if (!out_f32) return launch_one<256, 256, 2, 4, false, false, false, 1>(p, num_cus, s);
-        if (p.N <= 32) return launch_one<128, 32, 4, 1, true, false, false, 2>(p, num_cus, s);
-        if (p.N <= 64) return launch_one<128, 64, 2, 2, true, false, false, 2>(p, num_cus, s);
-        return launch_one<128, 128, 2, 2, true, false, false, 2>(p, num_cus, s);
+        // 128-row tiles when they still fill the chip twice over, else 32-row tiles: the K loop of such a
+        // skinny GEMM is latency bound, so the number of tiles in flight is what streams x
+        const bool tall = (int64_t)ceil_div(p.M, 128) * ceil_div(p.N, 128) >= 2 * (int64_t)num_cus;
+        // 32-row tiles run four LDS stages deep (three K tiles in flight per block)
+        if (p.N <= 32)
+            return tall ? launch_one<128, 32, 4, 1, true, false, false, 2>(p, num_cus, s)
+                        : launch_one<32, 32, 1, 1, true, false, false, 2, 4>(p, num_cus, s);
+        if (p.N <= 64)
+            return tall ? launch_one<128, 64, 2, 2, true, false, false, 2>(p, num_cus, s)
+                        : launch_one<32, 64, 1, 2, true, false, false, 2, 4>(p, num_cus, s);
+        return tall ? launch_one<128, 128, 2, 2, true, false, false, 2>(p, num_cus, s)
+                    : launch_one<32, 128, 1, 4, true, false, false, 2, 4>(p, num_cus, s);
     }
     if (out_f32) {
         set_error("grouped bf16 GEMM is only instantiated for bf16 output");

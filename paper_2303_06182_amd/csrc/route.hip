@@ -18,7 +18,10 @@ static constexpr int kWave = 64;
 // go to the lower expert index (inside a lane indices ascend with the register slot, across
 // lanes the butterfly compares (value, index)).
 // ------------------------------------------------------------------------------------------------
-template <int G, int V>
+// VEC: lane `sub` instead holds the 16-byte groups sub, sub+G, ... of the row (4 logits each, E a
+// multiple of 4), so every lane has V/4 float4 loads in flight; slot i of the lane is expert
+// (i/4)*4G + 4*sub + i%4, still ascending with i.
+template <int G, int V, bool VEC>
 __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
                                                         int renorm, int32_t *__restrict__ idx,
                                                         float *__restrict__ w)
@@ -28,17 +31,31 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
     const int t = blockIdx.x * TOK_PER_BLOCK + threadIdx.x / G;
     const bool live = t < T;
     const float NEG_INF = -__builtin_huge_valf();
+    auto expert_of = [&](int i) { return VEC ? (i >> 2) * (4 * G) + 4 * sub + (i & 3) : sub + i * G; };
 
     float v[V];
+    if (VEC) {
 #pragma unroll
-    for (int i = 0; i < V; ++i) {
-        const int e = sub + i * G;
-        v[i] = (live && e < E) ? logits[(int64_t)t * E + e] : NEG_INF;
+        for (int q = 0; q < V / 4; ++q) {
+            const int e0 = (q * G + sub) * 4;
+            float4 f = make_float4(NEG_INF, NEG_INF, NEG_INF, NEG_INF);
+            if (live && e0 < E) f = *reinterpret_cast<const float4 *>(logits + (int64_t)t * E + e0);
+            v[(4 * q + 0) % V] = f.x;
+            v[(4 * q + 1) % V] = f.y;
+            v[(4 * q + 2) % V] = f.z;
+            v[(4 * q + 3) % V] = f.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const int e = sub + i * G;
+            v[i] = (live && e < E) ? logits[(int64_t)t * E + e] : NEG_INF;
+        }
     }
-    uint32_t taken = 0;  // bit i: register slot i already selected
+    uint32_t taken = 0;  // bit i: register slot i already selected (or beyond E)
 #pragma unroll
     for (int i = 0; i < V; ++i)
-        if (sub + i * G >= E) taken |= 1u << i;
+        if (expert_of(i) >= E) taken |= 1u << i;
 
     float sel_v[MOE_MAX_K];
     int sel_e[MOE_MAX_K];
@@ -54,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
             const bool free_slot = !((taken >> i) & 1u);
             if (free_slot && (be == 0x7fffffff || v[i] > bv)) {
                 bv = v[i];
-                be = sub + i * G;
+                be = expert_of(i);
             }
         }
 #pragma unroll
@@ -74,7 +91,11 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
         be = __shfl(be, base, kWave);
         sel_v[j] = bv;
         sel_e[j] = be;
-        if (be != 0x7fffffff && (be % G) == sub) taken |= 1u << (be / G);
+        if (be != 0x7fffffff) {
+            const int owner = VEC ? (be % (4 * G)) >> 2 : be % G;
+            const int slot = VEC ? (be / (4 * G)) * 4 + (be & 3) : be / G;
+            if (owner == sub) taken |= 1u << slot;
+        }
     }
 
     // gate weights in fp32: exp(l - max) over the selected (renorm) or over all experts
@@ -88,7 +109,7 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
         float part = 0.f;
 #pragma unroll
         for (int i = 0; i < V; ++i)
-            if (sub + i * G < E) part += expf(v[i] - m);
+            if (expert_of(i) < E) part += expf(v[i] - m);
 #pragma unroll
         for (int off = G / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, kWave);
         denom = part;
@@ -104,13 +125,13 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
     }
 }
 
-template <int G, int V>
+template <int G, int V, bool VEC>
 static int launch_topk_t(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w,
                          hipStream_t s)
 {
     const int tpb = kThreads / G;
     ProfScope ps("topk", s);
-    hipLaunchKernelGGL((topk_kernel<G, V>), dim3(ceil_div(T, tpb)), dim3(kThreads), 0, s, logits, T, E, k, renorm,
+    hipLaunchKernelGGL((topk_kernel<G, V, VEC>), dim3(ceil_div(T, tpb)), dim3(kThreads), 0, s, logits, T, E, k, renorm,
                        idx, w);
     MOE_LAUNCH_CHECK("topk_kernel");
     return MOE_OK;
@@ -119,15 +140,25 @@ static int launch_topk_t(const float *logits, int T, int E, int k, int renorm, i
 int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s)
 {
     if (T == 0) return MOE_OK;
-    if (E <= 4) return launch_topk_t<4, 1>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 8) return launch_topk_t<8, 1>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 16) return launch_topk_t<16, 1>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 32) return launch_topk_t<32, 1>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 64) return launch_topk_t<64, 1>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 128) return launch_topk_t<64, 2>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 256) return launch_topk_t<64, 4>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 512) return launch_topk_t<64, 8>(logits, T, E, k, renorm, idx, w, s);
-    return launch_topk_t<64, 16>(logits, T, E, k, renorm, idx, w, s);
+    if (E % 4 == 0) {  // rows are 16-byte aligned: vector loads, fewer lanes per token
+        if (E <= 8) return launch_topk_t<2, 4, true>(logits, T, E, k, renorm, idx, w, s);
+        if (E <= 16) return launch_topk_t<4, 4, true>(logits, T, E, k, renorm, idx, w, s);
+        if (E <= 32) return launch_topk_t<8, 4, true>(logits, T, E, k, renorm, idx, w, s);
+        if (E <= 64) return launch_topk_t<16, 4, true>(logits, T, E, k, renorm, idx, w, s);
+        if (E <= 128) return launch_topk_t<16, 8, true>(logits, T, E, k, renorm, idx, w, s);
+        if (E <= 256) return launch_topk_t<16, 16, true>(logits, T, E, k, renorm, idx, w, s);
+        if (E <= 512) return launch_topk_t<32, 16, true>(logits, T, E, k, renorm, idx, w, s);
+        return launch_topk_t<64, 16, true>(logits, T, E, k, renorm, idx, w, s);
+    }
+    if (E <= 4) return launch_topk_t<4, 1, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 8) return launch_topk_t<8, 1, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 16) return launch_topk_t<16, 1, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 32) return launch_topk_t<32, 1, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 64) return launch_topk_t<64, 1, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 128) return launch_topk_t<64, 2, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 256) return launch_topk_t<64, 4, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E <= 512) return launch_topk_t<64, 8, false>(logits, T, E, k, renorm, idx, w, s);
+    return launch_topk_t<64, 16, false>(logits, T, E, k, renorm, idx, w, s);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -208,6 +239,7 @@ __global__ __launch_bounds__(1024) void route_scan_kernel(int32_t *__restrict__ 
     if (threadIdx.x == 0) offsets[E] = total;
 }
 
+template <int KMAX>
 __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__restrict__ idx, int T, int E, int k,
                                                               const int32_t *__restrict__ offsets,
                                                               const int32_t *__restrict__ block_base,
@@ -219,10 +251,10 @@ __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__r
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
     const int t = blockIdx.x * kThreads + threadIdx.x;
-    int ej[MOE_MAX_K];
-    int rank[MOE_MAX_K];
+    int ej[KMAX];
+    int rank[KMAX];
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_K; ++j) {
+    for (int j = 0; j < KMAX; ++j) {
         ej[j] = (t < T && j < k) ? clamp_expert(idx[(int64_t)t * k + j], E) : -1;
         rank[j] = 0;
     }
@@ -230,13 +262,13 @@ __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__r
     for (int e = 0; e < E; ++e) {
         int slot = -1;
 #pragma unroll
-        for (int j = 0; j < MOE_MAX_K; ++j)
+        for (int j = 0; j < KMAX; ++j)
             if (ej[j] == e) slot = j;
         const uint64_t mask = __ballot(slot >= 0);
         if (slot >= 0) {
             const int r = __popcll(mask & lt_mask);
 #pragma unroll
-            for (int j = 0; j < MOE_MAX_K; ++j)
+            for (int j = 0; j < KMAX; ++j)
                 if (j == slot) rank[j] = r;
         }
         if (lane == 0) wave_cnt[wave][e] = __popcll(mask);
@@ -254,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__r
     __syncthreads();
     if (t < T) {
 #pragma unroll
-        for (int j = 0; j < MOE_MAX_K; ++j) {
+        for (int j = 0; j < KMAX; ++j) {
             if (j < k) {
                 const int e = ej[j];
                 const int r = offsets[e] + block_base[(int64_t)blockIdx.x * E + e] + wave_cnt[wave][e] + rank[j];
@@ -277,8 +309,19 @@ int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32
     hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, nblk, E, EP, T * k, counts, offsets);
     MOE_LAUNCH_CHECK("route_scan_kernel");
     if (T > 0) {
-        hipLaunchKernelGGL(route_rank_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets, block_hist,
-                           dst_row, src_tok);
+        // KMAX = slots a lane compares per expert: the smallest instantiation that holds k
+        if (k <= 1)
+            hipLaunchKernelGGL(route_rank_kernel<1>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
+                               block_hist, dst_row, src_tok);
+        else if (k <= 2)
+            hipLaunchKernelGGL(route_rank_kernel<2>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
+                               block_hist, dst_row, src_tok);
+        else if (k <= 4)
+            hipLaunchKernelGGL(route_rank_kernel<4>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
+                               block_hist, dst_row, src_tok);
+        else
+            hipLaunchKernelGGL(route_rank_kernel<MOE_MAX_K>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
+                               block_hist, dst_row, src_tok);
         MOE_LAUNCH_CHECK("route_rank_kernel");
     }
     return MOE_OK;
