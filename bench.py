@@ -27,6 +27,19 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 VALU_F32_PEAK_TFLOPS = 157.3  # fp32 vector
 
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
+# 1 GiB calibration kernel: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE; see profiles/moe_layer_forward_*.txt).
+# Counter runs cannot be made from inside this script, so the figures of the committed profiles are
+# quoted for the kernels they cover; any other (workload, kernel) reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("lm", "expert_gemm1"): 876500 * 1024, ("lm", "expert_gemm2"): 859616 * 1024,
+    ("lm", "dispatch"): 49376 * 1024, ("lm", "combine"): 49514 * 1024, ("lm", "gate_gemm"): 19592 * 1024,
+    ("skewed_large", "expert_gemm1"): 16712609 * 1024, ("skewed_large", "expert_gemm2"): 15288476 * 1024,
+    ("skewed_large", "dispatch"): 788756 * 1024, ("skewed_large", "combine"): 790982 * 1024,
+    ("skewed_large", "gate_gemm"): 299303 * 1024,
+}
+
+
 def kernel_models(w, counts):
     """Algorithmic bytes / flops per launch of every kernel of the layer (what the method
     itself must move or compute, independent of how the kernels are written)."""
@@ -104,6 +117,9 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
     for kname, v in acc.items():
         ms = float(np.mean(v))
         kernels[kname] = roofline_entry(kname, models[kname], ms, w.dtype)
+        kernels[kname]["traffic"] = MEASURED_TRAFFIC_BYTES.get((name, kname))
+        kernels[kname]["algorithmic_bytes"] = models[kname]["bytes"]
+        kernels[kname]["algorithmic_flops"] = models[kname]["flops"]
     dominant = max(kernels.values(), key=lambda r: r["avg_ms"])
     res = dict(workload=name, T=w.T, D=w.D, F=w.F, E=w.E, k=w.k, dtype=w.dtype,
                ms_per_step=ms_per_step, tokens_per_s=w.T / (ms_per_step * 1e-3),
@@ -247,10 +263,11 @@ def main():
         "config": {"workload": args.config, "T": main_res["T"], "D": main_res["D"], "F": main_res["F"],
                    "E": main_res["E"], "k": main_res["k"], "max_expert_share": main_res["max_expert_share"],
                    "idle_experts": main_res["idle_experts"], "workspace_bytes": main_res["workspace_bytes"]},
-        "roofline": {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "avg_ms")},
+        "roofline": {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "avg_ms",
+                                                "algorithmic_bytes", "algorithmic_flops")},
         "cpu_baseline": cpu,
         "kernels": {k: dict(avg_ms=v["avg_ms"], bound=v["bound"], achieved=v["achieved"], unit=v["unit"],
-                            frac=v["frac"]) for k, v in main_res["kernels"].items()},
+                            frac=v["frac"], traffic=v["traffic"]) for k, v in main_res["kernels"].items()},
         "also": also,
         "static_baseline": static,
         "paper_context": "paper reports only relative whole-model speedups of dynamic over static gating on "
