@@ -53,6 +53,15 @@ __device__ __forceinline__ uint32_t to_bf16(float f)
     return u >> 16;
 }
 __device__ __forceinline__ float from_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+// two fp32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    const bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
 
 struct TileInfo {
     int row0, row_end, expert, n0;
@@ -173,7 +182,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
 
     // ---- epilogue: acc[mi][ni] holds D[column][row]: lane -> row (lane & 31) of block mi, registers
     // 4g..4g+3 -> columns 8g + 4*(lane >> 5) + 0..3 of block ni
+    // A wave tile of 256 accumulator registers lives in the accumulation registers (AGPRs); left to
+    // itself the compiler copies all of them to VGPRs at the loop exit and spills.  Reading them one
+    // by one where they are used keeps the epilogue at a handful of VGPRs.  The reads are opaque to
+    // the compiler's hazard handling, so the MFMA -> accumulator-read distance is padded by hand.
+    constexpr bool ACC_IN_AGPR = MI * NI * 16 > 128;
     auto epilogue = [&](const TileInfo &t) {
+        if constexpr (ACC_IN_AGPR) {
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        }
         const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
         if (bias) bias += (int64_t)t.expert * p.strideBias;
         const bool vec_ok = !OUT_F32 || ((p.ldc & 3) == 0 && (p.N & 3) == 0);
@@ -189,7 +206,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                     if (col >= p.N) continue;
                     float v[4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = acc[mi][ni][4 * g + i];
+                    for (int i = 0; i < 4; ++i) {
+                        if constexpr (ACC_IN_AGPR)
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[i]) : "a"(acc[mi][ni][4 * g + i]));
+                        else
+                            v[i] = acc[mi][ni][4 * g + i];
+                    }
                     if (bias) {
                         if (col + 3 < p.N) {
                             const uint2 bb = *reinterpret_cast<const uint2 *>(bias + col);
@@ -224,11 +246,86 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                     } else {
                         // bf16 output: N and ldc are multiples of 8 here, so the 4 columns exist
                         uint2 o;
-                        o.x = to_bf16(v[0]) | (to_bf16(v[1]) << 16);
-                        o.y = to_bf16(v[2]) | (to_bf16(v[3]) << 16);
+                        o.x = pack_bf16(v[0], v[1]);
+                        o.y = pack_bf16(v[2], v[3]);
                         *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(p.C) + (int64_t)row * p.ldc + col) = o;
                     }
                 }
+            }
+        }
+    };
+
+    // ---- bf16 epilogue through LDS: a wave turns one 32-row strip of its tile (32 x WTN outputs)
+    // into bf16, parks it in LDS and stores it back out with 16 bytes per lane, so a store
+    // instruction writes whole contiguous row segments instead of 32 scattered 16-byte pieces.
+    // The strip lives in the rows of the just-consumed LDS stage that THIS wave's own loads fill
+    // (rows (wave*IT + i)*8..+7), so no other wave ever writes there and no barrier is needed: the
+    // wave's own LDS accesses execute in order, all waves finished reading that stage before the
+    // last barrier, and the wave's next load into it is issued after the strip's last read returned.
+    // 16-byte chunk c of strip row r sits at chunk position c ^ (r mod chunks-per-row).
+    constexpr int STRIP_ROW_BYTES = WTN * 2;
+    constexpr int STRIP_BYTES = 32 * STRIP_ROW_BYTES;
+    constexpr bool STRIP_IN_A = A_IT * 1024 >= STRIP_BYTES;
+    constexpr bool STRIP_IN_B = !STRIP_IN_A && B_IT * 1024 >= STRIP_BYTES;
+    constexpr bool LDS_EPILOGUE = !OUT_F32 && KFULL && (STRIP_IN_A || STRIP_IN_B);
+    auto epilogue_lds = [&](const TileInfo &t, int free_stage) {
+        constexpr int CPRW = STRIP_ROW_BYTES / 16;  // chunks per strip row
+        constexpr int RPI = 64 / CPRW;              // strip rows one 64-lane access covers
+        if constexpr (ACC_IN_AGPR) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        uint8_t *stg = reinterpret_cast<uint8_t *>(STRIP_IN_A ? sA + free_stage * BM * BK + wave * A_IT * 8 * BK
+                                                             : sB + free_stage * BN * BK + wave * B_IT * 8 * BK);
+        const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
+        if (bias) bias += (int64_t)t.expert * p.strideBias;
+        const int r = lane & 31;
+        const int col_base = t.n0 + wn * WTN;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int cl = ni * 32 + 8 * g + 4 * (lane >> 5);  // column inside the strip
+                    const int col = col_base + cl;
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if constexpr (ACC_IN_AGPR)
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[i]) : "a"(acc[mi][ni][4 * g + i]));
+                        else
+                            v[i] = acc[mi][ni][4 * g + i];
+                    }
+                    if (bias && col < p.N) {  // N is a multiple of 8 for bf16 output: the 4 columns exist together
+                        const uint2 bb = *reinterpret_cast<const uint2 *>(bias + col);
+                        v[0] += __uint_as_float(bb.x << 16);
+                        v[1] += __uint_as_float(bb.x & 0xffff0000u);
+                        v[2] += __uint_as_float(bb.y << 16);
+                        v[3] += __uint_as_float(bb.y & 0xffff0000u);
+                    }
+                    if (p.bias_f32 && col < p.N) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] += p.bias_f32[col + i];
+                    }
+                    if (RELU) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.f ? v[i] : 0.f;
+                    }
+                    uint2 o;
+                    o.x = pack_bf16(v[0], v[1]);
+                    o.y = pack_bf16(v[2], v[3]);
+                    const int pos = (cl >> 3) ^ (r & (CPRW - 1));
+                    *reinterpret_cast<uint2 *>(stg + r * STRIP_ROW_BYTES + pos * 16 + ((cl >> 2) & 1) * 8) = o;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 32 / RPI; ++j) {
+                const int rr = j * RPI + lane / CPRW;
+                const int ch = lane % CPRW;
+                const uint4 val =
+                    *reinterpret_cast<const uint4 *>(stg + rr * STRIP_ROW_BYTES + ((ch ^ (rr & (CPRW - 1))) * 16));
+                const int row = t.row0 + wm * WTM + mi * 32 + rr;
+                const int col = col_base + ch * 8;
+                if (row < t.row_end && col < p.N)
+                    *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(p.C) + (int64_t)row * p.ldc + col) = val;
             }
         }
     };
@@ -241,33 +338,45 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         // The base is fixed per instruction, so the swizzle is applied on the global side: the lane
         // that lands in chunk slot (L & 7) of row r fetches K chunk (L & 7) ^ ((r >> 1) & 7).
         // Instruction i of wave w fills rows (w*IT + i)*8 .. +7.
-        const uint16_t *a_ptr[A_IT];
-        const uint16_t *b_ptr[B_IT];
+        // Per lane: one 64-bit base per operand (row of instruction 0) plus a 32-bit element offset per
+        // instruction -- 64-bit pointers per instruction would not fit the register file next to
+        // the accumulators of the largest tile.
+        const uint16_t *a_base, *b_base;
+        int a_off[A_IT], b_off[B_IT];
         auto set_ptrs = [&](const TileInfo &ti) {
             const uint16_t *Bg = Bg0 + (int64_t)ti.expert * p.strideB;
+            int gr0 = 0, gn0 = 0;
 #pragma unroll
             for (int i = 0; i < A_IT; ++i) {
                 const int r = (wave * A_IT + i) * 8 + (lane >> 3);
                 const int kc = (lane & 7) ^ ((r >> 1) & 7);
                 const int gr = min(ti.row0 + r, ti.row_end - 1);  // rows past the end repeat the last one
-                a_ptr[i] = Ag + (int64_t)gr * p.lda + kc * 8;
+                if (i == 0) {
+                    gr0 = gr;
+                    a_base = Ag + (int64_t)gr * p.lda;
+                }
+                a_off[i] = (gr - gr0) * p.lda + kc * 8;
             }
 #pragma unroll
             for (int i = 0; i < B_IT; ++i) {
                 const int r = (wave * B_IT + i) * 8 + (lane >> 3);
                 const int kc = (lane & 7) ^ ((r >> 1) & 7);
                 const int gn = min(ti.n0 + r, p.N - 1);
-                b_ptr[i] = Bg + (int64_t)gn * p.ldb + kc * 8;
+                if (i == 0) {
+                    gn0 = gn;
+                    b_base = Bg + (int64_t)gn * p.ldb;
+                }
+                b_off[i] = (gn - gn0) * p.ldb + kc * 8;
             }
         };
         auto issue = [&](int kt, int buf) {
 #pragma unroll
             for (int i = 0; i < A_IT; ++i)
-                __builtin_amdgcn_global_load_lds((const glb_void *)(a_ptr[i] + kt * BK),
+                __builtin_amdgcn_global_load_lds((const glb_void *)(a_base + (a_off[i] + kt * BK)),
                                                  (lds_void *)(sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < B_IT; ++i)
-                __builtin_amdgcn_global_load_lds((const glb_void *)(b_ptr[i] + kt * BK),
+                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * BK)),
                                                  (lds_void *)(sB + buf * BN * BK + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
         };
         // The loads run STAGES-1 K tiles ahead of the MFMAs along the block's whole sequence of
@@ -322,7 +431,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 stage_barrier();
                 stage = (stage + 1 == STAGES) ? 0 : stage + 1;
             }
-            epilogue(t);
+            if constexpr (LDS_EPILOGUE)
+                epilogue_lds(t, stage == 0 ? STAGES - 1 : stage - 1);  // the stage the last K tile was read from
+            else
+                epilogue(t);
             seq += slots;
             if (!seq_ok(seq)) break;
             t = tile_info(seq);
@@ -430,7 +542,7 @@ static int forced_variant()
     if (v < 0) {
         const char *e = getenv("MOE355_GEMM_VARIANT");  // tuning override, 0 / unset = automatic
         v = e ? atoi(e) : 0;
-        if (v != 1 && v != 2 && v != 3 && v != 5) v = 0;
+        if (v != 1 && v != 2 && v != 3 && v != 5 && v != 7) v = 0;
     }
     return v;
 }
@@ -495,7 +607,9 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
         return MOE_ERR_UNSUPPORTED;
     }
     switch (block_m) {
-    case 256: return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
+    case 256:
+        if (forced_variant() == 7) return launch_grouped<256, 256, 2, 2, 1>(p, relu, num_cus, s);
+        return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
     case 128: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
     case 64: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
     case 32: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
