@@ -45,6 +45,7 @@ typedef __attribute__((address_space(1))) void glb_void;
 
 static constexpr int BK = 64;
 static constexpr int GROUP_M = 4;
+static constexpr int REG_STAGED = 0;  // value of the STAGES template argument that selects the register-staged pipeline
 
 __device__ __forceinline__ uint32_t to_bf16(float f)
 {
@@ -78,9 +79,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "tile rows must split evenly over threads");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
-    uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [STAGES][BM*64]
-    uint16_t *sB = sA + STAGES * BM * BK;                   // [STAGES][BN*64]
-    static_assert(STAGES >= 2, "at least two LDS stages");
+    // STAGES == REG_STAGED selects the register-staged pipeline (two LDS buffers)
+    constexpr bool RSTAGE = STAGES == REG_STAGED;
+    constexpr int NSTAGE = RSTAGE ? 2 : STAGES;
+    uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [NSTAGE][BM*64]
+    uint16_t *sB = sA + NSTAGE * BM * BK;                   // [NSTAGE][BN*64]
+    static_assert(NSTAGE >= 2, "at least two LDS stages");
+    static_assert(!RSTAGE || KFULL, "the register-staged pipeline needs K to be a multiple of the K tile");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -399,6 +404,120 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             __builtin_amdgcn_sched_barrier(0);
         };
         constexpr int LPS = A_IT + B_IT;             // load instructions per wave per stage
+        if constexpr (RSTAGE) {
+            // ---- register-staged pipeline.  A vector-memory instruction costs the issuing wave
+            // about one MFMA slot and the CU's address unit 16 clocks, so the loads of a K tile
+            // must neither come as one burst (every wave stalls in the queue while the matrix
+            // units idle) nor late (two LDS buffers leave no slack for their latency).  Here the
+            // LPS loads of K tile i+2 go into registers, one behind every (MFMAs per K tile / LPS)-th
+            // MFMA of iteration i; one iteration later, at the same slot, the register is written
+            // to the LDS buffer of tile i+1 (ds_write_b128, 1 KB contiguous per wave instruction)
+            // and immediately refilled.  Every load has a whole iteration to land, the address unit
+            // sees an even stream, and the LDS buffer written in an iteration is the one nobody
+            // reads until the barrier that ends it.
+            constexpr int KS = BK / 16, NM = MI * NI, NR = MI + NI, TM = KS * NM;
+            int l_seq = seq, l_kt = 0;
+            bool l_more = true;
+            set_ptrs(t);
+            uint4 R[LPS];
+            auto gload = [&](int i) -> uint4 {
+                const uint16_t *g = i < A_IT ? a_base + (a_off[i] + l_kt * BK) : b_base + (b_off[i - A_IT] + l_kt * BK);
+                return *reinterpret_cast<const uint4 *>(g);
+            };
+            auto lds_put = [&](int buf, int i, const uint4 &v) {
+                uint16_t *d = i < A_IT ? sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK
+                                       : sB + buf * BN * BK + (wave * B_IT + (i - A_IT)) * 8 * BK;
+                *reinterpret_cast<uint4 *>(d + lane * 8) = v;
+            };
+            auto advance = [&]() {
+                if (l_more && ++l_kt == KT) {
+                    if (seq_ok(l_seq + slots)) {
+                        l_seq += slots;
+                        l_kt = 0;
+                        set_ptrs(tile_info(l_seq));
+                    } else {
+                        l_more = false;
+                        l_kt = KT - 1;  // past the end: re-read the last K tile, never used
+                    }
+                }
+            };
+            bf16x8 af[2][MI], bfr[2][NI];
+            auto read_one = [&](int buf, int ks, int set, int m) {
+                const int chunkpos = ((ks * 2 + frag_half) ^ swz) << 3;
+                if (m < MI)
+                    af[set][m] = *reinterpret_cast<const bf16x8 *>(sA + buf * BM * BK + (wm * WTM + frag_row + m * 32) * BK +
+                                                                   chunkpos);
+                else
+                    bfr[set][m - MI] = *reinterpret_cast<const bf16x8 *>(
+                        sB + buf * BN * BK + (wn * WTN + frag_row + (m - MI) * 32) * BK + chunkpos);
+            };
+            // the ds_writes of this iteration must be complete before anyone reads the buffer
+            auto rs_sync = [&]() {
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            // One K tile out of LDS buffer cur; the instruction order is pinned MFMA by MFMA.
+            auto compute_rs = [&](int cur) {
+                const int nxt = cur ^ 1;
+#pragma unroll
+                for (int m = 0; m < NR; ++m) read_one(cur, 0, 0, m);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) {
+                        if (ks + 1 < KS) {  // fragment f of the next K-step is read behind MFMA f * NM / NR
+#pragma unroll
+                            for (int f = 0; f < NR; ++f)
+                                if (f * NM / NR == m) read_one(cur, ks + 1, (ks + 1) & 1, f);
+                        }
+                        const int mi = m / NI, ni = m % NI;
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][ni], af[ks & 1][mi],
+                                                                              acc[mi][ni], 0, 0, 0);
+                        const int gm = ks * NM + m;
+#pragma unroll
+                        for (int i = 0; i < LPS; ++i) {
+                            if ((i * TM + TM / 2) / LPS == gm) {  // slot i sits behind MFMA number (i + 1/2) * TM / LPS
+                                lds_put(nxt, i, R[i]);
+                                R[i] = gload(i);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                advance();
+                rs_sync();
+            };
+            // prologue: K tile 0 -> LDS buffer 0, K tile 1 -> registers
+#pragma unroll
+            for (int i = 0; i < LPS; ++i) R[i] = gload(i);
+            advance();
+#pragma unroll
+            for (int i = 0; i < LPS; ++i) lds_put(0, i, R[i]);
+#pragma unroll
+            for (int i = 0; i < LPS; ++i) R[i] = gload(i);
+            advance();
+            rs_sync();
+            int cur = 0;
+            while (true) {
+                zero_acc();
+                for (int kt = 0; kt < KT; ++kt) {
+                    compute_rs(cur);
+                    cur ^= 1;
+                }
+                if constexpr (LDS_EPILOGUE)
+                    epilogue_lds(t, cur ^ 1);  // the buffer the last K tile was read from
+                else
+                    epilogue(t);
+                seq += slots;
+                if (!seq_ok(seq)) break;
+                t = tile_info(seq);
+            }
+            return;
+        }
         constexpr int WAITN = (STAGES - 2) * LPS;
         int l_seq = seq, l_kt = 0, l_stage = 0;
         bool l_more = true;
@@ -505,7 +624,7 @@ static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + BN) * BK * sizeof(uint16_t);
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES>;
     static int blocks_per_cu = 0;  // per instantiation
     if (blocks_per_cu == 0) {
@@ -528,21 +647,25 @@ static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
 template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, int MINB, int STAGES = 2>
 static int launch_one(const GemmParams &p, int num_cus, hipStream_t s)
 {
-    // K a multiple of the K tile: direct-to-LDS main loop, no tail predicate; the register-staged
-    // fallback always uses two stages
+    // K a multiple of the K tile: pipelined main loop without a tail predicate; the K-tail path
+    // always uses two LDS stages
     return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true, MINB, STAGES>(p, num_cus, s)
                            : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB, 2>(p, num_cus, s);
 }
 
-// Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves)
-//   1: 128x128, 4 waves   2: 64x128, 4 waves   3: 32x128, 4 waves   5: 256x256, 8 waves
+// Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves, pipeline)
+//   8: 256x256, 8 waves, register-staged    10: 128x128, 4 waves, register-staged
+//   5: 256x256, 8 waves, direct-to-LDS       1: 128x128, 4 waves, direct-to-LDS
+//   2: 64x128, 4 waves, direct-to-LDS        3: 32x128, 4 waves, direct-to-LDS
+// The automatic choice takes 8 / 10 / 2 / 3 by the average number of rows per expert; 5 and 1 are
+// kept for comparison runs.
 static int forced_variant()
 {
     static int v = -1;
     if (v < 0) {
         const char *e = getenv("MOE355_GEMM_VARIANT");  // tuning override, 0 / unset = automatic
         v = e ? atoi(e) : 0;
-        if (v != 1 && v != 2 && v != 3 && v != 5 && v != 7) v = 0;
+        if (v != 1 && v != 2 && v != 3 && v != 5 && v != 8 && v != 10) v = 0;
     }
     return v;
 }
@@ -550,7 +673,7 @@ static int forced_variant()
 static int variant_block_m(int v)
 {
     switch (v) {
-    case 1: return 128;
+    case 1: case 10: return 128;
     case 2: return 64;
     case 3: return 32;
     default: return 256;
@@ -562,8 +685,8 @@ static int pick_variant(int64_t n_rows, int E)
     const int f = forced_variant();
     if (f) return f;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
-    if (avg >= 192) return 5;
-    if (avg >= 96) return 1;
+    if (avg >= 192) return 8;
+    if (avg >= 96) return 10;
     if (avg >= 48) return 2;
     return 3;
 }
@@ -588,7 +711,7 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
             return MOE_ERR_UNSUPPORTED;
         }
         // bf16 output: the dense mask multiplications of the static-capacity baseline
-        if (!out_f32) return launch_one<256, 256, 2, 4, false, false, false, 1>(p, num_cus, s);
+        if (!out_f32) return launch_one<256, 256, 2, 4, false, false, false, 1, REG_STAGED>(p, num_cus, s);
         // 128-row tiles when they still fill the chip twice over, else 32-row tiles: the K loop of such a
         // skinny GEMM is latency bound, so the number of tiles in flight is what streams x
         const bool tall = (int64_t)ceil_div(p.M, 128) * ceil_div(p.N, 128) >= 2 * (int64_t)num_cus;
@@ -608,9 +731,11 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
     }
     switch (block_m) {
     case 256:
-        if (forced_variant() == 7) return launch_grouped<256, 256, 2, 2, 1>(p, relu, num_cus, s);
-        return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
-    case 128: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
+        if (forced_variant() == 5) return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
+        return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
+    case 128:
+        if (forced_variant() == 1) return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
+        return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(p, relu, num_cus, s);
     case 64: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
     case 32: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
     default:
