@@ -18,12 +18,28 @@
 // different chunk positions, so fragment reads are conflict free (measured: 4 clk per
 // ds_read_b128 against 6 clk with an (r & 7) swizzle).
 //
-// Pipeline: STAGES LDS stages (2 for the big tiles, more for the small, latency-bound ones).  K
-// tiles go straight from global memory into LDS (global_load_lds_dwordx4, no register staging):
-// the loads run STAGES-1 K tiles ahead of the MFMAs and are waited for (vmcnt) only at the barrier
-// that ends an iteration.  Inside a K tile
-// the fragments of K-step ks+1 are read while the MFMAs of K-step ks issue (the instruction order
-// is pinned with sched_group_barrier, otherwise the compiler sinks the reads next to their use).
+// Two K pipelines, chosen per tile shape (template argument STAGES):
+//  * direct-to-LDS (small tiles, the gate): STAGES LDS stages; K tiles go straight from global
+//    memory into LDS (global_load_lds_dwordx4, no register staging), the loads run STAGES-1 K
+//    tiles ahead of the MFMAs and are waited for (vmcnt) only at the barrier that ends an
+//    iteration.  Several such blocks share a CU, so one block's load burst and barrier hide
+//    behind another block's MFMAs.
+//  * register-staged (256- and 128-row tiles, one or two blocks per CU): measured on gfx950, a
+//    vector-memory instruction costs the issuing wave 20-30 clocks of MFMA issue and the CU's
+//    address unit 16 clocks, so a K tile's loads issued as one burst stall every wave while the
+//    matrix units idle, and with only two 64 KB stages in LDS they cannot be issued late either.
+//    Here the loads of K tile i+2 go into registers one by one between the MFMAs of iteration i,
+//    are written to the other LDS buffer at the same slot of iteration i+1 and the register is
+//    refilled at once: every load has a full iteration to land and the address unit sees an
+//    even stream.
+// In both, the fragments of K-step ks+1 are read while the MFMAs of K-step ks issue (the
+// instruction order is pinned with sched_group_barrier / sched_barrier, otherwise the compiler
+// sinks the reads next to their use).
+//
+// Epilogue (bf16 output): each wave converts a 32-row strip of its tile, parks it in the LDS rows
+// only this wave's loads ever fill, and writes it out with 16 bytes per lane, i.e. whole
+// contiguous row segments per store instruction; the scattered form (16 bytes per row per
+// instruction) cost up to a fifth of a tile's time.
 //
 // Launch: PERSISTENT.  The grid is (CUs x resident blocks per CU); workgroups are handed to the 8
 // XCDs round-robin and each XCD has its own L2, so XCD x walks the contiguous range
@@ -657,8 +673,9 @@ static int launch_one(const GemmParams &p, int num_cus, hipStream_t s)
 //   8: 256x256, 8 waves, register-staged    10: 128x128, 4 waves, register-staged
 //   5: 256x256, 8 waves, direct-to-LDS       1: 128x128, 4 waves, direct-to-LDS
 //   2: 64x128, 4 waves, direct-to-LDS        3: 32x128, 4 waves, direct-to-LDS
-// The automatic choice takes 8 / 10 / 2 / 3 by the average number of rows per expert; 5 and 1 are
-// kept for comparison runs.
+// The automatic choice goes by the average number of rows per expert; 5 and 1 are kept for
+// comparison runs.  (A 128x256 shape, meant to quantise better over the CUs when a GEMM has only
+// one or two 256x256 tiles per CU, measured 16 % slower per flop and lost even there.)
 static int forced_variant()
 {
     static int v = -1;
@@ -670,7 +687,7 @@ static int forced_variant()
     return v;
 }
 
-static int variant_block_m(int v)
+int gemm_bf16_variant_block_m(int v)
 {
     switch (v) {
     case 1: case 10: return 128;
@@ -680,8 +697,10 @@ static int variant_block_m(int v)
     }
 }
 
-static int pick_variant(int64_t n_rows, int E)
+int gemm_bf16_variant(int64_t n_rows, int E, int N, int num_cus)
 {
+    (void)N;
+    (void)num_cus;
     const int f = forced_variant();
     if (f) return f;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
@@ -691,8 +710,6 @@ static int pick_variant(int64_t n_rows, int E)
     return 3;
 }
 
-int gemm_bf16_block_m(int64_t n_rows, int E) { return variant_block_m(pick_variant(n_rows, E)); }
-
 template <int BM, int BN, int WM, int WN, int MINB, int STAGES = 2>
 static int launch_grouped(const GemmParams &p, bool relu, int num_cus, hipStream_t s)
 {
@@ -701,7 +718,7 @@ static int launch_grouped(const GemmParams &p, bool relu, int num_cus, hipStream
 }
 
 // Dispatch over the instantiated shapes.
-int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
+int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f32, bool relu, int num_cus,
                      hipStream_t s)
 {
     if (!grouped) {
@@ -729,17 +746,15 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f3
         set_error("grouped bf16 GEMM is only instantiated for bf16 output");
         return MOE_ERR_UNSUPPORTED;
     }
-    switch (block_m) {
-    case 256:
-        if (forced_variant() == 5) return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
-        return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
-    case 128:
-        if (forced_variant() == 1) return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
-        return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(p, relu, num_cus, s);
-    case 64: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
-    case 32: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
+    switch (variant) {
+    case 8: return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
+    case 10: return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(p, relu, num_cus, s);
+    case 5: return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
+    case 1: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
+    case 2: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
+    case 3: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
     default:
-        set_error("unsupported GEMM block_m %d", block_m);
+        set_error("unsupported grouped GEMM variant %d", variant);
         return MOE_ERR_UNSUPPORTED;
     }
 }

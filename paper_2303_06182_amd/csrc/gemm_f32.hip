@@ -109,12 +109,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p)
     }
 }
 
-int launch_gemm_f32(const GemmParams &p, bool grouped, int block_m, bool relu, hipStream_t s)
+int gemm_f32_block_m() { return FBM; }
+
+int launch_gemm_f32(const GemmParams &p, bool grouped, bool relu, hipStream_t s)
 {
-    if (grouped && block_m != FBM) {
-        set_error("fp32 grouped GEMM needs block_m = %d", FBM);
-        return MOE_ERR_UNSUPPORTED;
-    }
     const int n_tiles = ceil_div(p.N, FBN);
     const int m_tiles = grouped ? p.max_m_tiles : ceil_div(p.M, FBM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;

@@ -55,22 +55,29 @@ ProfScope::~ProfScope()
     if (slot >= 0 && g_prof) (void)hipEventRecord(g_prof->stop[slot], stream);
 }
 
-int launch_gemm_bf16(const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
+int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f32, bool relu, int num_cus,
                      hipStream_t s);
-int gemm_bf16_block_m(int64_t n_rows, int E);
-int launch_gemm_f32(const GemmParams &p, bool grouped, int block_m, bool relu, hipStream_t s);
+int gemm_bf16_variant(int64_t n_rows, int E, int N, int num_cus);
+int gemm_bf16_variant_block_m(int variant);
+int launch_gemm_f32(const GemmParams &p, bool grouped, bool relu, hipStream_t s);
+int gemm_f32_block_m();
 
-int gemm_block_m(int dtype, int64_t n_rows, int E)
+int gemm_variant(int dtype, int64_t n_rows, int E, int N, int num_cus)
 {
-    return dtype == MOE_DTYPE_BF16 ? gemm_bf16_block_m(n_rows, E) : 64;
+    return dtype == MOE_DTYPE_BF16 ? gemm_bf16_variant(n_rows, E, N, num_cus) : 0;
 }
 
-int launch_gemm(int dtype, const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu, int num_cus,
+int gemm_variant_block_m(int dtype, int variant)
+{
+    return dtype == MOE_DTYPE_BF16 ? gemm_bf16_variant_block_m(variant) : gemm_f32_block_m();
+}
+
+int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool out_f32, bool relu, int num_cus,
                 hipStream_t s)
 {
     ProfScope ps(p.name ? p.name : (!grouped ? "gate_gemm" : (relu ? "expert_gemm1" : "expert_gemm2")), s);
-    if (dtype == MOE_DTYPE_BF16) return launch_gemm_bf16(p, grouped, block_m, out_f32, relu, num_cus, s);
-    return launch_gemm_f32(p, grouped, block_m, relu, s);  // fp32 storage: C is fp32 either way
+    if (dtype == MOE_DTYPE_BF16) return launch_gemm_bf16(p, grouped, variant, out_f32, relu, num_cus, s);
+    return launch_gemm_f32(p, grouped, relu, s);  // fp32 storage: C is fp32 either way
 }
 
 // ---- workspace ---------------------------------------------------------------------------------
@@ -231,9 +238,13 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offset
 {
     const moe_config_t &c = h->cfg;
     if (n_rows == 0) return MOE_OK;
-    const int bm = gemm_block_m(c.dtype, n_rows, c.E);
-    const int max_tiles = (int)(n_rows / bm) + c.E + 1;
-    int rc = launch_tile_map(offsets, c.E, bm, tile_expert, tile_row, num_tiles, max_tiles, s);
+    // each GEMM picks its own tile shape (N differs: F for the first, D for the second); the tile
+    // map is rebuilt between them only when the M tile height differs
+    const int v1 = gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus);
+    const int v2 = gemm_variant(c.dtype, n_rows, c.E, c.D, h->num_cus);
+    const int bm1 = gemm_variant_block_m(c.dtype, v1), bm2 = gemm_variant_block_m(c.dtype, v2);
+    int max_tiles = (int)(n_rows / bm1) + c.E + 1;
+    int rc = launch_tile_map(offsets, c.E, bm1, tile_expert, tile_row, num_tiles, max_tiles, s);
     if (rc != MOE_OK) return rc;
 
     GemmParams p;
@@ -256,8 +267,14 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offset
     p.ldc = c.F;
     p.N = c.F;
     p.K = c.D;
-    rc = launch_gemm(c.dtype, p, true, bm, false, true, h->num_cus, s);
+    rc = launch_gemm(c.dtype, p, true, v1, false, true, h->num_cus, s);
     if (rc != MOE_OK) return rc;
+    if (bm2 != bm1) {
+        max_tiles = (int)(n_rows / bm2) + c.E + 1;
+        rc = launch_tile_map(offsets, c.E, bm2, tile_expert, tile_row, num_tiles, max_tiles, s);
+        if (rc != MOE_OK) return rc;
+        p.max_m_tiles = max_tiles;
+    }
     // Yp = H * W2[e]^T + b2[e]
     p.A = hbuf;
     p.lda = c.F;
@@ -270,7 +287,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offset
     p.ldc = c.D;
     p.N = c.D;
     p.K = c.F;
-    return launch_gemm(c.dtype, p, true, bm, false, false, h->num_cus, s);
+    return launch_gemm(c.dtype, p, true, v2, false, false, h->num_cus, s);
 }
 
 static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,

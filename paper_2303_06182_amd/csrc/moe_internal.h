@@ -109,12 +109,14 @@ struct GemmParams {
     const char *name;            // host only: label of the launch for the event profiler (may be NULL)
 };
 
-// Rows per M tile the grouped bf16 / fp32 GEMMs will use for a problem with `avg_rows` rows per
-// expert; the tile map must be built with the same value.
-int gemm_block_m(int dtype, int64_t n_rows, int E);
+// Tile shape (an opaque variant id) the grouped GEMM uses for n_rows rows over E experts and N
+// output columns, and the M tile height of a variant; the tile map must be built with that height.
+int gemm_variant(int dtype, int64_t n_rows, int E, int N, int num_cus);
+int gemm_variant_block_m(int dtype, int variant);
 
-// out_f32: C is fp32 (else elem); relu: max(.,0) before the store.
-int launch_gemm(int dtype, const GemmParams &p, bool grouped, int block_m, bool out_f32, bool relu,
+// variant: from gemm_variant (grouped) or 0 (plain).  out_f32: C is fp32 (else elem); relu:
+// max(.,0) before the store.
+int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool out_f32, bool relu,
                 int num_cus, hipStream_t s);
 
 // Tile map for the grouped GEMM from the device-side offsets (one block).
