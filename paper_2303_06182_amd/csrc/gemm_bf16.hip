@@ -111,9 +111,25 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     const int KT = (K + BK - 1) / BK;
 
     // ---- the block's sequence of tiles -----------------------------------------------------------
-    const int n_tiles = (p.N + BN - 1) / BN;
+    // Tail splitting (grouped GEMM over 256x256 tiles): a persistent launch of G blocks runs
+    // ceil(tiles / G) rounds, and when the last round is mostly empty the chip idles for a whole
+    // tile time.  So the launch with tail_mode 1 stops at the last whole round, and a second launch
+    // (tail_mode 2, a smaller tile shape, more blocks per CU) runs the L leftover tiles as SUB
+    // sub-tiles each.  Both compute the same cut from the device-side tile count; the split is taken
+    // when the sub-tiles' lower per-flop rate (about 0.69) still beats one more whole round.
+    constexpr int PT = 256;                             // parent tile edge
+    constexpr int SUB_N = PT / BN > 0 ? PT / BN : 1;    // sub-tiles per parent along N
+    constexpr int SUB = (PT / BM > 0 ? PT / BM : 1) * SUB_N;
+    const bool tail_sub = GROUPED && p.tail_mode == 2;
+    const int n_tiles = (p.N + (tail_sub ? PT : BN) - 1) / (tail_sub ? PT : BN);  // of the tile list's geometry
     const int m_tiles = GROUPED ? p.num_tiles[0] : (p.M + BM - 1) / BM;
-    const int live = m_tiles * n_tiles;        // logical tiles
+    int live = m_tiles * n_tiles;              // logical tiles
+    int cut = 0;                               // first parent tile of the tail
+    if (GROUPED && p.tail_mode != 0) {
+        const int left = live % p.main_slots;
+        cut = (left > 0 && left * 29 < p.main_slots * 20) ? live - left : live;
+        live = tail_sub ? (live - cut) * SUB : cut;
+    }
     const int chunk = (live + 7) >> 3;         // per XCD
     const int xcd = blockIdx.x & 7;
     const int slots = gridDim.x >> 3;          // blocks per XCD (grid is a multiple of 8)
@@ -122,7 +138,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     // logical tile -> (M tile, N tile): groups of GROUP_M M-tiles (the last group may be narrower),
     // inside a group the M index runs fastest
     auto tile_info = [&](int sq) {
-        const int lid = xcd * chunk + sq;
+        int lid = xcd * chunk + sq;
+        int sub = 0;
+        if (tail_sub) {
+            sub = lid % SUB;
+            lid = cut + lid / SUB;
+        }
         const int per_group = GROUP_M * n_tiles;
         const int grp = lid / per_group;
         const int within = lid - grp * per_group;
@@ -140,6 +161,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             t.row_end = p.M;
         }
         t.n0 = nt * BN;
+        if (tail_sub) {  // sub-tile (sub / SUB_N, sub % SUB_N) of the 256x256 parent
+            t.row0 += (sub / SUB_N) * BM;
+            t.n0 = nt * PT + (sub % SUB_N) * BN;
+        }
         return t;
     };
     if (!seq_ok(seq)) return;
@@ -635,8 +660,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
 }
 
 template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES>
-static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
+static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *main_grid)
 {
+    GemmParams p = p_in;
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
@@ -652,21 +678,34 @@ static int launch_k(const GemmParams &p, int num_cus, hipStream_t s)
     }
     // persistent grid: every resident slot of the chip, but never more blocks than upper-bound tiles
     int64_t grid = (int64_t)num_cus * blocks_per_cu;
-    const int64_t tiles = (int64_t)m_tiles * n_tiles;
+    int64_t tiles = (int64_t)m_tiles * n_tiles;
+    if (p.tail_mode == 2) {
+        // max_m_tiles counts 256-row parents; at most (main_slots * 20 - 1) / 29 of the parent tiles are left over
+        p.main_slots = *main_grid;
+        const int64_t parents = (int64_t)m_tiles * ceil_div(p.N, 256);
+        const int64_t left_max = ((int64_t)p.main_slots * 20 - 1) / 29;
+        tiles = (parents < left_max ? parents : left_max) * ((256 / BM) * (256 / BN));
+        if (tiles <= 0) return MOE_OK;
+    }
     if (grid > tiles) grid = tiles;
     grid = align_up(grid, 8);
+    if (p.tail_mode == 1) {
+        p.main_slots = (int)grid;
+        *main_grid = (int)grid;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, s, p);
     MOE_LAUNCH_CHECK("gemm_bf16_kernel");
     return MOE_OK;
 }
 
 template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, int MINB, int STAGES = 2>
-static int launch_one(const GemmParams &p, int num_cus, hipStream_t s)
+static int launch_one(const GemmParams &p, int num_cus, hipStream_t s, int *main_grid = nullptr)
 {
     // K a multiple of the K tile: pipelined main loop without a tail predicate; the K-tail path
     // always uses two LDS stages
-    return (p.K % BK == 0) ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true, MINB, STAGES>(p, num_cus, s)
-                           : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB, 2>(p, num_cus, s);
+    return (p.K % BK == 0)
+               ? launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, true, MINB, STAGES>(p, num_cus, s, main_grid)
+               : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB, 2>(p, num_cus, s, main_grid);
 }
 
 // Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves, pipeline)
@@ -685,6 +724,16 @@ static int forced_variant()
         if (v != 1 && v != 2 && v != 3 && v != 5 && v != 8 && v != 10) v = 0;
     }
     return v;
+}
+
+static bool no_tail_split()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("MOE355_GEMM_NO_TAIL_SPLIT");  // comparison runs
+        v = (e && atoi(e) != 0) ? 1 : 0;
+    }
+    return v == 1;
 }
 
 int gemm_bf16_variant_block_m(int v)
@@ -711,10 +760,10 @@ int gemm_bf16_variant(int64_t n_rows, int E, int N, int num_cus)
 }
 
 template <int BM, int BN, int WM, int WN, int MINB, int STAGES = 2>
-static int launch_grouped(const GemmParams &p, bool relu, int num_cus, hipStream_t s)
+static int launch_grouped(const GemmParams &p, bool relu, int num_cus, hipStream_t s, int *main_grid = nullptr)
 {
-    return relu ? launch_one<BM, BN, WM, WN, false, true, true, MINB, STAGES>(p, num_cus, s)
-                : launch_one<BM, BN, WM, WN, false, false, true, MINB, STAGES>(p, num_cus, s);
+    return relu ? launch_one<BM, BN, WM, WN, false, true, true, MINB, STAGES>(p, num_cus, s, main_grid)
+                : launch_one<BM, BN, WM, WN, false, false, true, MINB, STAGES>(p, num_cus, s, main_grid);
 }
 
 // Dispatch over the instantiated shapes.
@@ -747,7 +796,17 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
         return MOE_ERR_UNSUPPORTED;
     }
     switch (variant) {
-    case 8: return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
+    case 8: {
+        // whole rounds as 256x256 tiles, the partly filled last round as 128x128 sub-tiles
+        if (p.K % BK != 0 || no_tail_split()) return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
+        GemmParams q = p;
+        int main_grid = 0;
+        q.tail_mode = 1;
+        int rc = launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(q, relu, num_cus, s, &main_grid);
+        if (rc != MOE_OK || main_grid == 0) return rc;
+        q.tail_mode = 2;
+        return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(q, relu, num_cus, s, &main_grid);
+    }
     case 10: return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(p, relu, num_cus, s);
     case 5: return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
     case 1: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);

@@ -106,6 +106,11 @@ struct GemmParams {
     const int32_t *tile_row;     // [max_m_tiles] first row of the tile
     const int32_t *num_tiles;    // [1]
     int max_m_tiles;             // host upper bound of *num_tiles (sizes the grid)
+    // tail splitting of a grouped GEMM over 256x256 tiles (0 = off): 1 = this launch runs the whole
+    // rounds of 256x256 tiles, 2 = this launch runs the tiles of the last, partly filled round as
+    // smaller sub-tiles; main_slots = grid size of the launch with tail_mode 1 (both need it)
+    int tail_mode;
+    int main_slots;
     const char *name;            // host only: label of the launch for the event profiler (may be NULL)
 };
 
