@@ -396,12 +396,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             for (int i = 0; i < A_IT; ++i) {
                 const int r = (wave * A_IT + i) * 8 + (lane >> 3);
                 const int kc = (lane & 7) ^ ((r >> 1) & 7);
-                const int gr = min(ti.row0 + r, ti.row_end - 1);  // rows past the end repeat the last one
+                int gr = min(ti.row0 + r, ti.row_end - 1);  // rows past the end repeat the last one
+                // dispatch fused into the load: the rows of the expert's batch are gathered straight
+                // from the token array (the launcher checked that rows * lda fits 31 bits)
+                if (GROUPED && p.a_rows) gr = p.a_rows[gr];
                 if (i == 0) {
                     gr0 = gr;
                     a_base = Ag + (int64_t)gr * p.lda;
                 }
-                a_off[i] = (gr - gr0) * p.lda + kc * 8;
+                a_off[i] = (gr - gr0) * (int)p.lda + kc * 8;
             }
 #pragma unroll
             for (int i = 0; i < B_IT; ++i) {
@@ -735,6 +738,9 @@ static bool no_tail_split()
     }
     return v == 1;
 }
+
+// every grouped bf16 shape reads A through per-lane row pointers when K is a multiple of the K tile
+bool gemm_bf16_variant_gathers(int variant, int K) { return variant != 0 && K % BK == 0; }
 
 int gemm_bf16_variant_block_m(int v)
 {

@@ -3,6 +3,7 @@
 // for the device, or reads device data on the host.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -61,6 +62,7 @@ int gemm_bf16_variant(int64_t n_rows, int E, int N, int num_cus);
 int gemm_bf16_variant_block_m(int variant);
 int launch_gemm_f32(const GemmParams &p, bool grouped, bool relu, hipStream_t s);
 int gemm_f32_block_m();
+bool gemm_bf16_variant_gathers(int variant, int K);
 
 int gemm_variant(int dtype, int64_t n_rows, int E, int N, int num_cus)
 {
@@ -232,9 +234,11 @@ static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const fl
 }
 
 // Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows, F] and the tile arrays are scratch.
-static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
-                          const void *b1, const void *b2, int64_t n_rows, void *yp, void *hbuf, int32_t *tile_expert,
-                          int32_t *tile_row, int32_t *num_tiles, hipStream_t s)
+// a_rows != NULL: xp is the token array and row r of the experts' input is its row a_rows[r]
+// (dispatch fused into the first GEMM's loads; the caller checked fused_dispatch_ok)
+static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows, const int32_t *offsets,
+                          const void *w1, const void *w2, const void *b1, const void *b2, int64_t n_rows, void *yp,
+                          void *hbuf, int32_t *tile_expert, int32_t *tile_row, int32_t *num_tiles, hipStream_t s)
 {
     const moe_config_t &c = h->cfg;
     if (n_rows == 0) return MOE_OK;
@@ -257,6 +261,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offset
     p.M = (int)n_rows;
     // H = relu(Xp * W1[e]^T + b1[e])
     p.A = xp;
+    p.a_rows = a_rows;
     p.lda = c.D;
     p.B = w1;
     p.ldb = c.D;
@@ -277,6 +282,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offset
     }
     // Yp = H * W2[e]^T + b2[e]
     p.A = hbuf;
+    p.a_rows = nullptr;
     p.lda = c.F;
     p.B = w2;
     p.ldb = c.F;
@@ -290,11 +296,25 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offset
     return launch_gemm(c.dtype, p, true, v2, false, false, h->num_cus, s);
 }
 
-static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1, const void *w2,
-                         const void *b1, const void *b2, int n_rows, void *yp, void *ws, hipStream_t s)
+// Can the first expert GEMM gather its rows from the token array (T tokens) itself?
+static bool fused_dispatch_ok(const moe_handle_t *h, int64_t T)
+{
+    static int off = -1;
+    if (off < 0) {
+        const char *e = getenv("MOE355_NO_FUSED_DISPATCH");  // comparison runs
+        off = (e && atoi(e) != 0) ? 1 : 0;
+    }
+    const moe_config_t &c = h->cfg;
+    if (off || c.dtype != MOE_DTYPE_BF16 || T * c.D >= ((int64_t)1 << 31)) return false;
+    return gemm_bf16_variant_gathers(gemm_variant(c.dtype, T * c.k, c.E, c.F, h->num_cus), c.D);
+}
+
+static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows, const int32_t *offsets,
+                         const void *w1, const void *w2, const void *b1, const void *b2, int n_rows, void *yp,
+                         void *ws, hipStream_t s)
 {
     const WsLayout L = ws_layout(h->cfg);
-    return run_expert_ffn(h, xp, offsets, w1, w2, b1, b2, n_rows, yp, at<void>(ws, L.h),
+    return run_expert_ffn(h, xp, a_rows, offsets, w1, w2, b1, b2, n_rows, yp, at<void>(ws, L.h),
                           at<int32_t>(ws, L.tile_expert), at<int32_t>(ws, L.tile_row), at<int32_t>(ws, L.num_tiles), s);
 }
 
@@ -531,7 +551,7 @@ int moe_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, cons
         return MOE_ERR_INVALID_ARG;
     int rc = check_ws(h, workspace, workspace_bytes);
     if (rc != MOE_OK) return rc;
-    return do_expert_ffn(h, xp, offsets, w1, w2, b1, b2, n_rows, yp, workspace, (hipStream_t)stream);
+    return do_expert_ffn(h, xp, nullptr, offsets, w1, w2, b1, b2, n_rows, yp, workspace, (hipStream_t)stream);
 }
 
 int moe_combine(moe_handle_t *h, const void *yp, const int32_t *dst_row, const float *topk_w, int32_t T, void *y,
@@ -589,9 +609,13 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
     if (rc != MOE_OK) return rc;
     rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, at<int32_t>(workspace, L.block_hist), s);
     if (rc != MOE_OK) return rc;
-    rc = launch_dispatch(c.dtype, x, dst_row, T, c.D, c.k, xp, s);
-    if (rc != MOE_OK) return rc;
-    rc = do_expert_ffn(h, xp, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
+    // dispatch: a scatter of its own, or folded into the first GEMM's row addressing (then Xp is never written)
+    const bool fused = fused_dispatch_ok(h, T);
+    if (!fused) {
+        rc = launch_dispatch(c.dtype, x, dst_row, T, c.D, c.k, xp, s);
+        if (rc != MOE_OK) return rc;
+    }
+    rc = do_expert_ffn(h, fused ? x : xp, fused ? src_tok : nullptr, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
     if (rc != MOE_OK) return rc;
     return launch_combine(c.dtype, yp, dst_row, w, T, c.D, c.k, y, s);
 }
@@ -720,7 +744,7 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
         if (rc != MOE_OK) return rc;
     }
     // every expert processes all of its `capacity` rows, zero rows included
-    rc = run_expert_ffn(h, xd, offsets_static, w1, w2, b1, b2, R, yd, at<void>(ws, L.hd),
+    rc = run_expert_ffn(h, xd, nullptr, offsets_static, w1, w2, b1, b2, R, yd, at<void>(ws, L.hd),
                         at<int32_t>(ws, L.tile_expert), at<int32_t>(ws, L.tile_row), at<int32_t>(ws, L.num_tiles), s);
     if (rc != MOE_OK) return rc;
     if (mode == MOE_STATIC_INDEXED) return launch_combine(c.dtype, yd, slot_row, w, T, c.D, c.k, y, s);

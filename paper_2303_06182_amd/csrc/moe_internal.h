@@ -91,6 +91,7 @@ __host__ __device__ static inline int ceil_div(int a, int b) { return (a + b - 1
 struct GemmParams {
     const void *A;       // [rows, K]
     int64_t lda;
+    const int32_t *a_rows;  // bf16 grouped kernels: logical row r of A is row a_rows[r] of the array (NULL = r)
     const void *B;       // [N, K] (plain) or [E, N, K] (grouped)
     int64_t ldb;
     int64_t strideB;     // elements between experts
@@ -118,6 +119,8 @@ struct GemmParams {
 // output columns, and the M tile height of a variant; the tile map must be built with that height.
 int gemm_variant(int dtype, int64_t n_rows, int E, int N, int num_cus);
 int gemm_variant_block_m(int dtype, int variant);
+// true when the variant's kernel can read its A rows through GemmParams::a_rows
+bool gemm_variant_gathers(int dtype, int variant);
 
 // variant: from gemm_variant (grouped) or 0 (plain).  out_f32: C is fp32 (else elem); relu:
 // max(.,0) before the store.
