@@ -205,6 +205,63 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
                              int32_t *dropped_count, const moe_routing_t *routing_out,
                              void *workspace, int64_t workspace_bytes, void *stream);
 
+/* ---- Expert Buffering (Sec. 6): expert parameters in host memory, a device cache of a few ----
+ * ---- experts, copies overlapped with expert computation                                   ---- */
+
+/* Cache management alone (host logic, no device work; Sec. 6 "Cache Management").  The experts
+ * with counts[e] > 0 are active and are visited in increasing id order: a resident expert is a
+ * hit; a miss goes to a free slot, else it replaces a victim -- residents that are not active in
+ * this batch first, then active ones, inside each class the one that entered the cache last
+ * (Last In, First Out; with 2 slots and experts (1,2,3) needed, 3 replaces 2 and 1 stays).
+ *   counts   [E] host int32
+ *   slot_of  [E] host int32 out: slot the expert runs from in this batch, -1 if not active
+ *   stage_of [E] host int32 out: execution stage, -1 if not active.  A victim that already ran
+ *            in this batch must finish before its slot is overwritten, so its replacement is one
+ *            stage later; stages never decrease along the id order; experts of one stage have
+ *            distinct slots
+ *   loads    [4*max_loads] host int32 out: (expert, slot, victim or -1, stage) per miss, in order
+ * Errors: MOE_ERR_INVALID_ARG for NULL arguments or a load list that is too short (n_loads then
+ * holds the needed length; the cache state has still advanced).  The object is owned by the
+ * caller and not thread safe. */
+typedef struct moe_cache_policy moe_cache_policy_t;
+int moe_cache_policy_create(int32_t E, int32_t slots, moe_cache_policy_t **out);
+int moe_cache_policy_destroy(moe_cache_policy_t *p);
+int moe_cache_policy_reset(moe_cache_policy_t *p); /* empty cache, zero statistics */
+int moe_cache_policy_step(moe_cache_policy_t *p, const int32_t *counts, int32_t *slot_of, int32_t *stage_of,
+                          int32_t *loads, int32_t max_loads, int32_t *n_loads, int32_t *n_stages);
+/* hits / misses since creation or reset (an access = one active expert of one batch);
+ * slot_expert [slots] host int32 (may be NULL) receives the expert held by every slot, -1 = free. */
+int moe_cache_policy_stats(const moe_cache_policy_t *p, int64_t *hits, int64_t *misses, int32_t *slot_expert);
+
+/* The device side of the buffer.  host_w1 [E,F,D] and host_w2 [E,D,F] (elem) stay in HOST memory
+ * owned by the caller -- pinned memory (hipHostMalloc), or the copies are not asynchronous -- and
+ * must stay valid and unchanged while the cache lives.  device_mem is device memory owned by the
+ * caller, at least moe_expert_cache_bytes(h, slots) bytes, 256-byte aligned: `slots` slots of one
+ * expert's W1 and W2 plus two small index arrays.  The object creates one copy stream (default
+ * priority) and a few events; destroy it before the handle. */
+typedef struct moe_expert_cache moe_expert_cache_t;
+int64_t moe_expert_cache_bytes(const moe_handle_t *h, int32_t slots);
+int moe_expert_cache_create(moe_handle_t *h, int32_t slots, const void *host_w1, const void *host_w2,
+                            void *device_mem, int64_t device_bytes, moe_expert_cache_t **out);
+int moe_expert_cache_destroy(moe_expert_cache_t *c);
+int moe_expert_cache_reset(moe_expert_cache_t *c); /* forget every resident expert, zero the statistics */
+/* hits, misses, bytes copied host to device, and stages executed, since creation or reset */
+int moe_expert_cache_stats(const moe_expert_cache_t *c, int64_t *hits, int64_t *misses, int64_t *bytes_copied,
+                           int64_t *stages);
+
+/* moe_layer_forward with buffered experts (Sec. 6): same result, bit for bit, as the plain call
+ * on the same parameters.  After the routing step the per-expert token counts are copied to the
+ * host and the call WAITS for `stream` once (the cache decision is host logic, as in the paper,
+ * where the counts reach the host with the first all-to-all); missing experts are then copied into
+ * their slots on the cache's copy stream while the experts that are already resident compute, and
+ * the expert FFN runs stage by stage (see moe_cache_policy_step) from the slots.  b1 [E,F] and
+ * b2 [E,D] (NULL or device memory) are not buffered.  Needs `slots` >= 1; a batch with more active
+ * experts than slots runs in several stages.  Calls on one cache must not overlap. */
+int moe_layer_forward_buffered(moe_handle_t *h, moe_expert_cache_t *cache, const void *x, const void *wg,
+                               const float *gate_bias, const void *b1, const void *b2, int32_t T, void *y,
+                               const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes,
+                               void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,9 @@ EXPORTS = [
     "moe_create", "moe_destroy", "moe_last_error", "moe_workspace_bytes", "moe_static_workspace_bytes",
     "moe_capacity", "moe_gate_topk", "moe_route_counts", "moe_dispatch", "moe_expert_ffn", "moe_combine",
     "moe_layer_forward", "moe_layer_forward_static", "moe_profile_begin", "moe_profile_end", "moe_profile_name",
+    "moe_cache_policy_create", "moe_cache_policy_destroy", "moe_cache_policy_reset", "moe_cache_policy_step",
+    "moe_cache_policy_stats", "moe_expert_cache_bytes", "moe_expert_cache_create", "moe_expert_cache_destroy",
+    "moe_expert_cache_reset", "moe_expert_cache_stats", "moe_layer_forward_buffered",
 ]
 
 
@@ -97,6 +100,30 @@ def load_library() -> ctypes.CDLL:
     lib.moe_profile_end.restype = ctypes.c_int
     lib.moe_profile_name.argtypes = [vp, i32]
     lib.moe_profile_name.restype = ctypes.c_char_p
+    pi32, pi64 = ctypes.POINTER(i32), ctypes.POINTER(i64)
+    lib.moe_cache_policy_create.argtypes = [i32, i32, ctypes.POINTER(vp)]
+    lib.moe_cache_policy_create.restype = ctypes.c_int
+    lib.moe_cache_policy_destroy.argtypes = [vp]
+    lib.moe_cache_policy_destroy.restype = ctypes.c_int
+    lib.moe_cache_policy_reset.argtypes = [vp]
+    lib.moe_cache_policy_reset.restype = ctypes.c_int
+    lib.moe_cache_policy_step.argtypes = [vp, pi32, pi32, pi32, pi32, i32, pi32, pi32]
+    lib.moe_cache_policy_step.restype = ctypes.c_int
+    lib.moe_cache_policy_stats.argtypes = [vp, pi64, pi64, pi32]
+    lib.moe_cache_policy_stats.restype = ctypes.c_int
+    lib.moe_expert_cache_bytes.argtypes = [vp, i32]
+    lib.moe_expert_cache_bytes.restype = i64
+    lib.moe_expert_cache_create.argtypes = [vp, i32, vp, vp, vp, i64, ctypes.POINTER(vp)]
+    lib.moe_expert_cache_create.restype = ctypes.c_int
+    lib.moe_expert_cache_destroy.argtypes = [vp]
+    lib.moe_expert_cache_destroy.restype = ctypes.c_int
+    lib.moe_expert_cache_reset.argtypes = [vp]
+    lib.moe_expert_cache_reset.restype = ctypes.c_int
+    lib.moe_expert_cache_stats.argtypes = [vp, pi64, pi64, pi64, pi64]
+    lib.moe_expert_cache_stats.restype = ctypes.c_int
+    lib.moe_layer_forward_buffered.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting), vp,
+                                               i64, vp]
+    lib.moe_layer_forward_buffered.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -266,3 +293,86 @@ class MoeLayer:
                                                  self._routing_struct(routing_out), _ptr(workspace),
                                                  workspace.numel(), _stream()))
         return y, dropped[:1]
+
+
+class CachePolicy:
+    """moe_cache_policy_*: the cache management of Expert Buffering alone (host logic, no GPU)."""
+
+    def __init__(self, E: int, slots: int):
+        self.lib = load_library()
+        self.E, self.slots = E, slots
+        self.p = ctypes.c_void_p()
+        _check(self.lib.moe_cache_policy_create(E, slots, ctypes.byref(self.p)))
+
+    def __del__(self):
+        if getattr(self, "p", None) is not None and self.p:
+            self.lib.moe_cache_policy_destroy(self.p)
+            self.p = None
+
+    def reset(self) -> None:
+        _check(self.lib.moe_cache_policy_reset(self.p))
+
+    def step(self, counts):
+        """counts: E host integers -> (slot_of, stage_of, loads, n_stages); loads = list of
+        (expert, slot, victim, stage)."""
+        E = self.E
+        c = (ctypes.c_int32 * E)(*[int(v) for v in counts])
+        slot_of, stage_of = (ctypes.c_int32 * E)(), (ctypes.c_int32 * E)()
+        loads = (ctypes.c_int32 * (4 * E))()
+        n_loads, n_stages = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(self.lib.moe_cache_policy_step(self.p, c, slot_of, stage_of, loads, E, ctypes.byref(n_loads),
+                                              ctypes.byref(n_stages)))
+        ll = [tuple(loads[4 * i + j] for j in range(4)) for i in range(n_loads.value)]
+        return list(slot_of), list(stage_of), ll, n_stages.value
+
+    def stats(self):
+        """-> (hits, misses, expert held by every slot)."""
+        h, m = ctypes.c_int64(0), ctypes.c_int64(0)
+        se = (ctypes.c_int32 * self.slots)()
+        _check(self.lib.moe_cache_policy_stats(self.p, ctypes.byref(h), ctypes.byref(m), se))
+        return h.value, m.value, list(se)
+
+
+class ExpertCache:
+    """moe_expert_cache_*: `slots` device slots in front of expert parameters kept in pinned host
+    memory (host_w1 [E,F,D], host_w2 [E,D,F], torch CPU tensors with pin_memory)."""
+
+    def __init__(self, layer: "MoeLayer", slots: int, host_w1: torch.Tensor, host_w2: torch.Tensor):
+        self.lib = layer.lib
+        self.layer = layer
+        self.slots = slots
+        if host_w1.device.type != "cpu" or host_w2.device.type != "cpu":
+            raise ValueError("host_w1 / host_w2 must be CPU tensors (pinned)")
+        self.host_w1, self.host_w2 = host_w1, host_w2  # kept alive
+        nbytes = int(self.lib.moe_expert_cache_bytes(layer.h, slots))
+        if nbytes < 0:
+            _check(nbytes)
+        self.device_mem = torch.empty(nbytes, dtype=torch.uint8, device=layer.device)
+        self.c = ctypes.c_void_p()
+        _check(self.lib.moe_expert_cache_create(layer.h, slots, host_w1.data_ptr(), host_w2.data_ptr(),
+                                                _ptr(self.device_mem), nbytes, ctypes.byref(self.c)))
+
+    def __del__(self):
+        if getattr(self, "c", None) is not None and self.c:
+            self.lib.moe_expert_cache_destroy(self.c)
+            self.c = None
+
+    def reset(self) -> None:
+        _check(self.lib.moe_expert_cache_reset(self.c))
+
+    def stats(self):
+        """-> dict(hits, misses, bytes_copied, stages)."""
+        v = [ctypes.c_int64(0) for _ in range(4)]
+        _check(self.lib.moe_expert_cache_stats(self.c, *[ctypes.byref(x) for x in v]))
+        return dict(hits=v[0].value, misses=v[1].value, bytes_copied=v[2].value, stages=v[3].value)
+
+    def moe_layer_forward_buffered(self, x, wg, gate_bias=None, b1=None, b2=None, y=None, routing_out=None):
+        L = self.layer
+        T = x.shape[0]
+        if y is None:
+            y = L._new((T, L.D), L.torch_dtype)
+        ws, wsb = L._ws()
+        _check(self.lib.moe_layer_forward_buffered(L.h, self.c, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(b1),
+                                                   _ptr(b2), T, _ptr(y), L._routing_struct(routing_out), ws, wsb,
+                                                   _stream()))
+        return y

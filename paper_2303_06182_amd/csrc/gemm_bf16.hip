@@ -390,7 +390,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         const uint16_t *a_base, *b_base;
         int a_off[A_IT], b_off[B_IT];
         auto set_ptrs = [&](const TileInfo &ti) {
-            const uint16_t *Bg = Bg0 + (int64_t)ti.expert * p.strideB;
+            // weights of expert e sit in slot b_slot[e] of the weight array when experts are buffered
+            const uint16_t *Bg = Bg0 + (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
             int gr0 = 0, gn0 = 0;
 #pragma unroll
             for (int i = 0; i < A_IT; ++i) {
@@ -608,7 +609,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         // chunk c = tid + i*THREADS; row = c >> 3, kc = c & 7
         const int kc = tid & 7;
         while (true) {
-            const uint16_t *Bg = Bg0 + (int64_t)t.expert * p.strideB;
+            const uint16_t *Bg = Bg0 + (int64_t)((GROUPED && p.b_slot) ? p.b_slot[t.expert] : t.expert) * p.strideB;
             const uint16_t *a_ptr[A_IT];
             const uint16_t *b_ptr[B_IT];
             int a_lds[A_IT], b_lds[B_IT];

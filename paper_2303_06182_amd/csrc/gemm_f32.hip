@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p)
     const int n0 = nt * FBN;
     const int K = p.K;
     const float *Ag = static_cast<const float *>(p.A);
-    const float *Bg = static_cast<const float *>(p.B) + (int64_t)expert * p.strideB;
+    const float *Bg = static_cast<const float *>(p.B) + (int64_t)((GROUPED && p.b_slot) ? p.b_slot[expert] : expert) * p.strideB;
 
     const int tid = threadIdx.x;
     const int lrow = tid >> 2;  // 0..63: tile row this thread copies

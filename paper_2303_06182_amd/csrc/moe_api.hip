@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "moe_internal.h"
 
@@ -233,10 +234,21 @@ static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const fl
     return launch_topk(logits, T, c.E, c.k, c.renormalize, idx, w, s);
 }
 
+// Options of the grouped FFN beyond the plain call.
+struct FfnExtra {
+    // xp is the token array and row r of the experts' input is its row a_rows[r] (dispatch fused
+    // into the first GEMM's loads; the caller checked fused_dispatch_ok)
+    const int32_t *a_rows = nullptr;
+    // expert buffering: w1 / w2 point at the first slot's W1 / W2, slots are slot_stride elements
+    // apart, expert e's weights are in slot b_slot[e], and only experts with stage_of[e] == stage run
+    const int32_t *b_slot = nullptr;
+    const int32_t *stage_of = nullptr;
+    int stage = 0;
+    int64_t slot_stride = 0;
+};
+
 // Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows, F] and the tile arrays are scratch.
-// a_rows != NULL: xp is the token array and row r of the experts' input is its row a_rows[r]
-// (dispatch fused into the first GEMM's loads; the caller checked fused_dispatch_ok)
-static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows, const int32_t *offsets,
+static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, const int32_t *offsets,
                           const void *w1, const void *w2, const void *b1, const void *b2, int64_t n_rows, void *yp,
                           void *hbuf, int32_t *tile_expert, int32_t *tile_row, int32_t *num_tiles, hipStream_t s)
 {
@@ -248,7 +260,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows
     const int v2 = gemm_variant(c.dtype, n_rows, c.E, c.D, h->num_cus);
     const int bm1 = gemm_variant_block_m(c.dtype, v1), bm2 = gemm_variant_block_m(c.dtype, v2);
     int max_tiles = (int)(n_rows / bm1) + c.E + 1;
-    int rc = launch_tile_map(offsets, c.E, bm1, tile_expert, tile_row, num_tiles, max_tiles, s);
+    int rc = launch_tile_map(offsets, c.E, bm1, tile_expert, tile_row, num_tiles, max_tiles, ex.stage_of, ex.stage, s);
     if (rc != MOE_OK) return rc;
 
     GemmParams p;
@@ -261,11 +273,12 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows
     p.M = (int)n_rows;
     // H = relu(Xp * W1[e]^T + b1[e])
     p.A = xp;
-    p.a_rows = a_rows;
+    p.a_rows = ex.a_rows;
     p.lda = c.D;
     p.B = w1;
+    p.b_slot = ex.b_slot;
     p.ldb = c.D;
-    p.strideB = (int64_t)c.F * c.D;
+    p.strideB = ex.b_slot ? ex.slot_stride : (int64_t)c.F * c.D;
     p.bias = b1;
     p.strideBias = c.F;
     p.C = hbuf;
@@ -276,7 +289,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows
     if (rc != MOE_OK) return rc;
     if (bm2 != bm1) {
         max_tiles = (int)(n_rows / bm2) + c.E + 1;
-        rc = launch_tile_map(offsets, c.E, bm2, tile_expert, tile_row, num_tiles, max_tiles, s);
+        rc = launch_tile_map(offsets, c.E, bm2, tile_expert, tile_row, num_tiles, max_tiles, ex.stage_of, ex.stage, s);
         if (rc != MOE_OK) return rc;
         p.max_m_tiles = max_tiles;
     }
@@ -286,7 +299,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows
     p.lda = c.F;
     p.B = w2;
     p.ldb = c.F;
-    p.strideB = (int64_t)c.D * c.F;
+    p.strideB = ex.b_slot ? ex.slot_stride : (int64_t)c.D * c.F;
     p.bias = b2;
     p.strideBias = c.D;
     p.C = yp;
@@ -309,12 +322,12 @@ static bool fused_dispatch_ok(const moe_handle_t *h, int64_t T)
     return gemm_bf16_variant_gathers(gemm_variant(c.dtype, T * c.k, c.E, c.F, h->num_cus), c.D);
 }
 
-static int do_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *a_rows, const int32_t *offsets,
+static int do_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, const int32_t *offsets,
                          const void *w1, const void *w2, const void *b1, const void *b2, int n_rows, void *yp,
                          void *ws, hipStream_t s)
 {
     const WsLayout L = ws_layout(h->cfg);
-    return run_expert_ffn(h, xp, a_rows, offsets, w1, w2, b1, b2, n_rows, yp, at<void>(ws, L.h),
+    return run_expert_ffn(h, xp, ex, offsets, w1, w2, b1, b2, n_rows, yp, at<void>(ws, L.h),
                           at<int32_t>(ws, L.tile_expert), at<int32_t>(ws, L.tile_row), at<int32_t>(ws, L.num_tiles), s);
 }
 
@@ -365,6 +378,43 @@ static StaticLayout static_layout(const moe_config_t &c, int64_t T, int64_t cap,
     }
     L.total = off;
     return L;
+}
+
+// ---- expert buffering (paper Sec. 6) ----------------------------------------------------------
+int cache_policy_step(moe_cache_policy *p, const int32_t *counts, int32_t *slot_of, int32_t *stage_of,
+                      int32_t *loads, int32_t max_loads, int32_t *n_loads, int32_t *n_stages);
+
+}  // namespace moe355
+
+struct moe_expert_cache {
+    moe_handle_t *h = nullptr;
+    moe_cache_policy_t *policy = nullptr;
+    int slots = 0;
+    const uint8_t *host_w1 = nullptr, *host_w2 = nullptr;
+    int64_t half_bytes = 0;        // one expert's W1 (= W2) in bytes
+    uint8_t *d_slots = nullptr;    // [slots][W1 | W2]
+    int32_t *d_slot_of = nullptr;  // [E] slot an active expert runs from
+    int32_t *d_stage = nullptr;    // [E] launch it runs in (2 * stage + missed), -1 idle
+    int32_t *pin = nullptr;        // pinned host: counts[E] | slot_of[E] | launch stage[E]
+    hipStream_t copy_stream = nullptr;
+    std::vector<hipEvent_t> events;  // grown on demand, reused by every call
+    std::vector<int32_t> stage_of, loads;
+    int64_t bytes_copied = 0, stages = 0;
+};
+
+namespace moe355 {
+
+static int64_t cache_index_bytes(const moe_config_t &c) { return align_up((int64_t)c.E * 4, 256); }
+
+static int cache_event(moe_expert_cache *c, size_t i, hipEvent_t *out)
+{
+    while (c->events.size() <= i) {
+        hipEvent_t e;
+        MOE_HIP_CHECK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c->events.push_back(e);
+    }
+    *out = c->events[i];
+    return MOE_OK;
 }
 
 }  // namespace moe355
@@ -551,7 +601,7 @@ int moe_expert_ffn(moe_handle_t *h, const void *xp, const int32_t *offsets, cons
         return MOE_ERR_INVALID_ARG;
     int rc = check_ws(h, workspace, workspace_bytes);
     if (rc != MOE_OK) return rc;
-    return do_expert_ffn(h, xp, nullptr, offsets, w1, w2, b1, b2, n_rows, yp, workspace, (hipStream_t)stream);
+    return do_expert_ffn(h, xp, FfnExtra(), offsets, w1, w2, b1, b2, n_rows, yp, workspace, (hipStream_t)stream);
 }
 
 int moe_combine(moe_handle_t *h, const void *yp, const int32_t *dst_row, const float *topk_w, int32_t T, void *y,
@@ -567,9 +617,15 @@ int moe_combine(moe_handle_t *h, const void *yp, const int32_t *dst_row, const f
     return launch_combine(h->cfg.dtype, yp, dst_row, topk_w, T, h->cfg.D, h->cfg.k, y, (hipStream_t)stream);
 }
 
-int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1,
-                      const void *w2, const void *b1, const void *b2, int32_t T, void *y,
-                      const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes, void *stream)
+static int buffered_expert_ffn(moe_handle_t *h, moe_expert_cache_t *cache, const void *xin, const int32_t *a_rows,
+                               const int32_t *counts, const int32_t *offsets, const void *b1, const void *b2,
+                               int32_t n_rows, void *yp, void *workspace, hipStream_t s);
+
+// cache == NULL: experts from w1 / w2 in device memory; else buffered (w1, w2 unused)
+static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const void *x, const void *wg,
+                              const float *gate_bias, const void *w1, const void *w2, const void *b1, const void *b2,
+                              int32_t T, void *y, const moe_routing_t *routing_out, void *workspace,
+                              int64_t workspace_bytes, void *stream)
 {
     g_err[0] = 0;
     ProfBind bind(h);
@@ -577,8 +633,8 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
     if (rc != MOE_OK) return rc;
     const bool empty = (T == 0);  // only counts and offsets are written then
     if (bad_ptr(x, "x", empty) || bad_ptr(wg, "wg", empty) || bad_ptr(gate_bias, "gate_bias", true) ||
-        bad_ptr(w1, "w1", empty) || bad_ptr(w2, "w2", empty) || bad_ptr(b1, "b1", true) || bad_ptr(b2, "b2", true) ||
-        bad_ptr(y, "y", empty))
+        bad_ptr(w1, "w1", empty || cache) || bad_ptr(w2, "w2", empty || cache) || bad_ptr(b1, "b1", true) ||
+        bad_ptr(b2, "b2", true) || bad_ptr(y, "y", empty))
         return MOE_ERR_INVALID_ARG;
     moe_routing_t r;
     memset(&r, 0, sizeof(r));
@@ -615,9 +671,209 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
         rc = launch_dispatch(c.dtype, x, dst_row, T, c.D, c.k, xp, s);
         if (rc != MOE_OK) return rc;
     }
-    rc = do_expert_ffn(h, fused ? x : xp, fused ? src_tok : nullptr, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
+    if (cache) {
+        rc = buffered_expert_ffn(h, cache, fused ? x : xp, fused ? src_tok : nullptr, counts, offsets, b1, b2,
+                                 T * c.k, yp, workspace, s);
+    } else {
+        FfnExtra ex;
+        ex.a_rows = fused ? src_tok : nullptr;
+        rc = do_expert_ffn(h, fused ? x : xp, ex, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
+    }
     if (rc != MOE_OK) return rc;
     return launch_combine(c.dtype, yp, dst_row, w, T, c.D, c.k, y, s);
+}
+
+int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1,
+                      const void *w2, const void *b1, const void *b2, int32_t T, void *y,
+                      const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    return layer_forward_impl(h, nullptr, x, wg, gate_bias, w1, w2, b1, b2, T, y, routing_out, workspace,
+                              workspace_bytes, stream);
+}
+
+// ---- expert buffering ------------------------------------------------------------------------
+int64_t moe_expert_cache_bytes(const moe_handle_t *h, int32_t slots)
+{
+    g_err[0] = 0;
+    if (!h || slots < 1) {
+        set_error("handle is NULL or slots = %d < 1", slots);
+        return MOE_ERR_INVALID_ARG;
+    }
+    const moe_config_t &c = h->cfg;
+    return 2 * cache_index_bytes(c) + (int64_t)slots * 2 * c.F * c.D * elem_size(c.dtype);
+}
+
+int moe_expert_cache_create(moe_handle_t *h, int32_t slots, const void *host_w1, const void *host_w2,
+                            void *device_mem, int64_t device_bytes, moe_expert_cache_t **out)
+{
+    g_err[0] = 0;
+    if (!h || !out || slots < 1) {
+        set_error("expert cache: handle or out is NULL, or slots = %d < 1", slots);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (bad_ptr(host_w1, "host_w1") || bad_ptr(host_w2, "host_w2") || bad_ptr(device_mem, "device_mem"))
+        return MOE_ERR_INVALID_ARG;
+    if (((uintptr_t)device_mem & 255) != 0 || device_bytes < moe_expert_cache_bytes(h, slots)) {
+        set_error("expert cache: device_mem must be 256-byte aligned and hold %lld bytes (got %lld)",
+                  (long long)moe_expert_cache_bytes(h, slots), (long long)device_bytes);
+        return MOE_ERR_WORKSPACE;
+    }
+    const moe_config_t &c = h->cfg;
+    moe_expert_cache *k = new (std::nothrow) moe_expert_cache;
+    if (!k) {
+        set_error("out of host memory");
+        return MOE_ERR_INVALID_ARG;
+    }
+    k->h = h;
+    k->slots = slots;
+    k->host_w1 = static_cast<const uint8_t *>(host_w1);
+    k->host_w2 = static_cast<const uint8_t *>(host_w2);
+    k->half_bytes = (int64_t)c.F * c.D * elem_size(c.dtype);
+    uint8_t *base = static_cast<uint8_t *>(device_mem);
+    k->d_slot_of = reinterpret_cast<int32_t *>(base);
+    k->d_stage = reinterpret_cast<int32_t *>(base + cache_index_bytes(c));
+    k->d_slots = base + 2 * cache_index_bytes(c);
+    k->stage_of.assign(c.E, -1);
+    k->loads.assign((size_t)4 * c.E, 0);
+    int rc = moe_cache_policy_create(c.E, slots, &k->policy);
+    if (rc == MOE_OK && hipSetDevice(h->device) != hipSuccess) rc = hip_failed(hipGetLastError(), "hipSetDevice");
+    if (rc == MOE_OK) {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&k->pin), (size_t)3 * c.E * 4, hipHostMallocDefault);
+        if (e != hipSuccess) rc = hip_failed(e, "hipHostMalloc");
+    }
+    if (rc == MOE_OK) {
+        hipError_t e = hipStreamCreateWithFlags(&k->copy_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) rc = hip_failed(e, "hipStreamCreateWithFlags");
+    }
+    if (rc != MOE_OK) {
+        moe_expert_cache_destroy(k);
+        return rc;
+    }
+    *out = k;
+    return MOE_OK;
+}
+
+int moe_expert_cache_destroy(moe_expert_cache_t *k)
+{
+    if (!k) return MOE_OK;
+    if (k->copy_stream) {
+        (void)hipStreamSynchronize(k->copy_stream);
+        (void)hipStreamDestroy(k->copy_stream);
+    }
+    for (hipEvent_t e : k->events) (void)hipEventDestroy(e);
+    if (k->pin) (void)hipHostFree(k->pin);
+    if (k->policy) moe_cache_policy_destroy(k->policy);
+    delete k;
+    return MOE_OK;
+}
+
+int moe_expert_cache_reset(moe_expert_cache_t *k)
+{
+    g_err[0] = 0;
+    if (!k) {
+        set_error("expert cache is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    k->bytes_copied = k->stages = 0;
+    return moe_cache_policy_reset(k->policy);
+}
+
+int moe_expert_cache_stats(const moe_expert_cache_t *k, int64_t *hits, int64_t *misses, int64_t *bytes_copied,
+                           int64_t *stages)
+{
+    g_err[0] = 0;
+    if (!k) {
+        set_error("expert cache is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (bytes_copied) *bytes_copied = k->bytes_copied;
+    if (stages) *stages = k->stages;
+    return moe_cache_policy_stats(k->policy, hits, misses, nullptr);
+}
+
+// The expert FFN from the cache's slots.  Host-side order of work:
+//   counts -> host (one wait for the stream), cache decision, index arrays -> device, then per
+//   policy stage: the stage's missing experts are copied on the copy stream (after everything that
+//   ran in earlier stages, whose slots they may take), the stage's resident experts compute
+//   meanwhile on the caller's stream, and the copied ones follow once their copy has landed.
+static int buffered_expert_ffn(moe_handle_t *h, moe_expert_cache_t *k, const void *xin, const int32_t *a_rows,
+                               const int32_t *counts, const int32_t *offsets, const void *b1, const void *b2,
+                               int32_t n_rows, void *yp, void *workspace, hipStream_t s)
+{
+    const moe_config_t &c = h->cfg;
+    if (k->h != h) {
+        set_error("the expert cache belongs to another handle");
+        return MOE_ERR_INVALID_ARG;
+    }
+    const int E = c.E;
+    int32_t *h_counts = k->pin, *h_slot = k->pin + E, *h_launch = k->pin + 2 * E;
+    MOE_HIP_CHECK(hipMemcpyAsync(h_counts, counts, (size_t)E * 4, hipMemcpyDeviceToHost, s));
+    MOE_HIP_CHECK(hipStreamSynchronize(s));  // also: every earlier call's reads of the slots are over
+    int32_t n_loads = 0, n_stages = 0;
+    int rc = cache_policy_step(k->policy, h_counts, h_slot, k->stage_of.data(), k->loads.data(), E, &n_loads, &n_stages);
+    if (rc != MOE_OK) return rc;
+    // launch index of an expert: 2 * stage for residents, 2 * stage + 1 for the ones copied in this batch
+    std::vector<int> in_launch((size_t)2 * (n_stages > 0 ? n_stages : 1), 0);
+    for (int e = 0; e < E; ++e) h_launch[e] = k->stage_of[e] < 0 ? -1 : 2 * k->stage_of[e];
+    for (int i = 0; i < n_loads; ++i) h_launch[k->loads[4 * i]] += 1;
+    for (int e = 0; e < E; ++e)
+        if (h_launch[e] >= 0) in_launch[h_launch[e]] += 1;
+    MOE_HIP_CHECK(hipMemcpyAsync(k->d_slot_of, h_slot, (size_t)E * 4, hipMemcpyHostToDevice, s));
+    MOE_HIP_CHECK(hipMemcpyAsync(k->d_stage, h_launch, (size_t)E * 4, hipMemcpyHostToDevice, s));
+
+    FfnExtra ex;
+    ex.a_rows = a_rows;
+    ex.b_slot = k->d_slot_of;
+    ex.stage_of = k->d_stage;
+    ex.slot_stride = 2 * (int64_t)c.F * c.D;
+    const void *w1 = k->d_slots, *w2 = k->d_slots + k->half_bytes;
+    hipEvent_t last_done = nullptr;
+    size_t ev = 0;
+    int li = 0;  // next entry of the load list (it is ordered by stage)
+    for (int st = 0; st < n_stages; ++st) {
+        hipEvent_t loaded = nullptr;
+        if (li < n_loads && k->loads[4 * li + 3] == st) {
+            if (last_done) MOE_HIP_CHECK(hipStreamWaitEvent(k->copy_stream, last_done, 0));
+            for (; li < n_loads && k->loads[4 * li + 3] == st; ++li) {
+                const int e = k->loads[4 * li], slot = k->loads[4 * li + 1];
+                uint8_t *dst = k->d_slots + (int64_t)slot * 2 * k->half_bytes;
+                MOE_HIP_CHECK(hipMemcpyAsync(dst, k->host_w1 + (int64_t)e * k->half_bytes, (size_t)k->half_bytes,
+                                             hipMemcpyHostToDevice, k->copy_stream));
+                MOE_HIP_CHECK(hipMemcpyAsync(dst + k->half_bytes, k->host_w2 + (int64_t)e * k->half_bytes,
+                                             (size_t)k->half_bytes, hipMemcpyHostToDevice, k->copy_stream));
+                k->bytes_copied += 2 * k->half_bytes;
+            }
+            rc = cache_event(k, ev++, &loaded);
+            if (rc != MOE_OK) return rc;
+            MOE_HIP_CHECK(hipEventRecord(loaded, k->copy_stream));
+        }
+        for (int part = 0; part < 2; ++part) {
+            if (in_launch[2 * st + part] == 0) continue;
+            if (part == 1) MOE_HIP_CHECK(hipStreamWaitEvent(s, loaded, 0));
+            ex.stage = 2 * st + part;
+            rc = do_expert_ffn(h, xin, ex, offsets, w1, w2, b1, b2, n_rows, yp, workspace, s);
+            if (rc != MOE_OK) return rc;
+            rc = cache_event(k, ev++, &last_done);
+            if (rc != MOE_OK) return rc;
+            MOE_HIP_CHECK(hipEventRecord(last_done, s));
+        }
+        k->stages += 1;
+    }
+    return MOE_OK;
+}
+
+int moe_layer_forward_buffered(moe_handle_t *h, moe_expert_cache_t *cache, const void *x, const void *wg,
+                               const float *gate_bias, const void *b1, const void *b2, int32_t T, void *y,
+                               const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes,
+                               void *stream)
+{
+    if (!cache) {
+        g_err[0] = 0;
+        set_error("expert cache is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    return layer_forward_impl(h, cache, x, wg, gate_bias, nullptr, nullptr, b1, b2, T, y, routing_out, workspace,
+                              workspace_bytes, stream);
 }
 
 int64_t moe_static_workspace_bytes(const moe_handle_t *h, int32_t T, int32_t capacity, int32_t mode)
@@ -744,7 +1000,7 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
         if (rc != MOE_OK) return rc;
     }
     // every expert processes all of its `capacity` rows, zero rows included
-    rc = run_expert_ffn(h, xd, nullptr, offsets_static, w1, w2, b1, b2, R, yd, at<void>(ws, L.hd),
+    rc = run_expert_ffn(h, xd, FfnExtra(), offsets_static, w1, w2, b1, b2, R, yd, at<void>(ws, L.hd),
                         at<int32_t>(ws, L.tile_expert), at<int32_t>(ws, L.tile_row), at<int32_t>(ws, L.num_tiles), s);
     if (rc != MOE_OK) return rc;
     if (mode == MOE_STATIC_INDEXED) return launch_combine(c.dtype, yd, slot_row, w, T, c.D, c.k, y, s);

@@ -52,6 +52,8 @@ struct moe_handle {
     moe355::Profiler prof;
 };
 
+struct moe_cache_policy;
+
 namespace moe355 {
 
 // ---- errors -----------------------------------------------------------------------------------
@@ -94,7 +96,8 @@ struct GemmParams {
     const int32_t *a_rows;  // bf16 grouped kernels: logical row r of A is row a_rows[r] of the array (NULL = r)
     const void *B;       // [N, K] (plain) or [E, N, K] (grouped)
     int64_t ldb;
-    int64_t strideB;     // elements between experts
+    int64_t strideB;     // elements between experts (between slots with b_slot)
+    const int32_t *b_slot;  // grouped: expert e's weights are slot b_slot[e] of B (NULL = e)
     const void *bias;    // elem [N] / [E,N], or NULL
     int64_t strideBias;
     const float *bias_f32;  // fp32 [N] or NULL (gate offsets)
@@ -128,8 +131,9 @@ int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool 
                 int num_cus, hipStream_t s);
 
 // Tile map for the grouped GEMM from the device-side offsets (one block).
+// stage_of != NULL: only the experts e with stage_of[e] == stage get tiles.
 int launch_tile_map(const int32_t *offsets, int E, int block_m, int32_t *tile_expert, int32_t *tile_row,
-                    int32_t *num_tiles, int max_m_tiles, hipStream_t s);
+                    int32_t *num_tiles, int max_m_tiles, const int32_t *stage_of, int stage, hipStream_t s);
 
 // ---- routing -------------------------------------------------------------------------------------
 int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s);

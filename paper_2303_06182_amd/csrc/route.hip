@@ -336,12 +336,13 @@ int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32
 __global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t *__restrict__ offsets, int E, int BM,
                                                         int32_t *__restrict__ tile_expert,
                                                         int32_t *__restrict__ tile_row,
-                                                        int32_t *__restrict__ num_tiles, int max_m_tiles)
+                                                        int32_t *__restrict__ num_tiles, int max_m_tiles,
+                                                        const int32_t *__restrict__ stage_of, int stage)
 {
     __shared__ int wave_tot[16];
     const int e = threadIdx.x;
     int row0 = 0, row1 = 0;
-    if (e < E) {
+    if (e < E && (!stage_of || stage_of[e] == stage)) {
         row0 = offsets[e];
         row1 = offsets[e + 1];
     }
@@ -370,11 +371,11 @@ __global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t *__restric
 }
 
 int launch_tile_map(const int32_t *offsets, int E, int block_m, int32_t *tile_expert, int32_t *tile_row,
-                    int32_t *num_tiles, int max_m_tiles, hipStream_t s)
+                    int32_t *num_tiles, int max_m_tiles, const int32_t *stage_of, int stage, hipStream_t s)
 {
     ProfScope ps("tile_map", s);
     hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(1024), 0, s, offsets, E, block_m, tile_expert, tile_row,
-                       num_tiles, max_m_tiles);
+                       num_tiles, max_m_tiles, stage_of, stage);
     MOE_LAUNCH_CHECK("tile_map_kernel");
     return MOE_OK;
 }

@@ -26,7 +26,7 @@ from __future__ import annotations
 
 import math
 from dataclasses import dataclass, replace
-from typing import Dict, Optional
+from typing import Dict, List, Optional
 
 import torch
 
@@ -164,6 +164,23 @@ def make_inputs(w: Workload, device="cpu", with_ffn_bias: bool = False) -> Dict[
     else:
         out["b1"] = None
         out["b2"] = None
+    return out
+
+
+def decode_steps(w: Workload, n_steps: int, rho: float = 0.9, device="cpu") -> List[torch.Tensor]:
+    """A synthetic sequence of decode steps for the expert-buffering workload: n_steps token
+    batches x_s [T,D] whose rows drift slowly (per element an AR(1) process of correlation rho
+    and the same marginal N(0, 0.02^2) as make_inputs' x), so that consecutive steps activate
+    overlapping sets of experts -- the temporal locality the paper's decoder traces show
+    (Sec. 6, "Cache Management").  Step 0 is make_inputs' x.  The recursion runs in fp32 and
+    every step is rounded once to the storage type."""
+    dt = w.torch_dtype
+    cur = normal(w.seed, STREAM_X, (w.T, w.D), 0.02, torch.float32, device)
+    out = [cur.to(dt)]
+    for s in range(1, n_steps):
+        noise = normal(w.seed, STREAM_X, (w.T, w.D), 0.02, torch.float32, device, attempt=1000 + s)
+        cur = rho * cur + math.sqrt(1.0 - rho * rho) * noise
+        out.append(cur.to(dt))
     return out
 
 
