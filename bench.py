@@ -185,6 +185,79 @@ def run_static(name, cfs, steps=3):
     return out
 
 
+def run_buffering(name, slots_list, n_steps, rho=0.9, tokens=(64, 16)):
+    """Expert Buffering (paper Sec. 6) on a decode-shaped workload: the expert parameters stay in
+    pinned host memory, `slots` experts fit on the device, a synthetic sequence of decode steps with
+    temporally correlated expert activity runs through moe_layer_forward_buffered.  Reports the
+    throughput, the cache's miss rate and the copied bytes per cache size, beside the plain call
+    (all experts resident) and beside what the oracle's simulator gives for the paper's policy,
+    FIFO, LRU and Belady's MIN on the same activity trace."""
+    import numpy as np
+    import torch
+    from oracle import expert_cache as ec
+    from paper_2303_06182_amd import binding, workloads as wl
+
+    base = wl.CONFIGS[name]
+    inp = wl.make_inputs(base, device="cpu")
+    hw1, hw2 = inp["w1"].pin_memory(), inp["w2"].pin_memory()
+    g = {k: (None if v is None else v.cuda()) for k, v in inp.items()}
+    results = {}
+    for T in tokens:  # the workload as defined, and a sparser step (a quarter of the tokens: about 3/4 of the experts idle)
+        results["T%d" % T] = _buffering_runs(base.scaled(T=T), g, hw1, hw2, slots_list, n_steps, rho)
+    return results
+
+
+def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho):
+    import numpy as np
+    import torch
+    from oracle import expert_cache as ec
+    from paper_2303_06182_amd import binding, workloads as wl
+
+    name = w.name
+    xs = [x.cuda() for x in wl.decode_steps(w, n_steps, rho)]
+    layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
+    y = torch.empty((w.T, w.D), dtype=w.torch_dtype, device="cuda")
+    routing = layer.empty_routing(w.T)
+    expert_bytes = 2 * w.F * w.D * (2 if w.dtype == "bf16" else 4)
+
+    trace = []
+    for x in xs:  # plain call: warm-up and the activity trace
+        layer.moe_layer_forward(x, g["wg"], g["w1"], g["w2"], g["gate_bias"], y=y, routing_out=routing)
+        trace.append(np.nonzero(routing["counts"].cpu().numpy())[0].tolist())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for x in xs:
+        layer.moe_layer_forward(x, g["wg"], g["w1"], g["w2"], g["gate_bias"], y=y)
+    torch.cuda.synchronize()
+    plain_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+    out = dict(workload=name, steps=n_steps, rho=rho, expert_bytes=expert_bytes,
+               active_experts_per_step=float(np.mean([len(t) for t in trace])),
+               distinct_experts=len(set(e for t in trace for e in t)),
+               all_resident=dict(ms_per_step=plain_ms, tokens_per_s=w.T / (plain_ms * 1e-3),
+                                 expert_bytes_on_device=w.E * expert_bytes),
+               slots={}, simulated_miss_rate={})
+    for slots in slots_list:
+        cache = binding.ExpertCache(layer, slots, hw1, hw2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for x in xs:
+            cache.moe_layer_forward_buffered(x, g["wg"], g["gate_bias"], y=y)
+        torch.cuda.synchronize()
+        secs = time.perf_counter() - t0
+        st = cache.stats()
+        ms = secs * 1e3 / n_steps
+        out["slots"][str(slots)] = dict(
+            ms_per_step=ms, tokens_per_s=w.T / (ms * 1e-3), hits=st["hits"], misses=st["misses"],
+            miss_rate=st["misses"] / max(1, st["hits"] + st["misses"]), bytes_copied=st["bytes_copied"],
+            copy_GBps_over_wall_time=st["bytes_copied"] / secs / 1e9, stages_per_step=st["stages"] / n_steps,
+            expert_bytes_on_device=slots * expert_bytes, device_bytes_saved=(w.E - slots) * expert_bytes)
+        out["simulated_miss_rate"][str(slots)] = {
+            pol: ec.simulate(trace, slots, pol)["miss_rate"] for pol in ec.POLICIES}
+        del cache
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(name, inp, budget_tokens):
     """The CPU oracle as it stands, timed on the host cores on a bounded sample of the same
     workload: the gate, top-k and routing for every token, the expert FFN and combine for
@@ -218,6 +291,8 @@ def main():
     ap.add_argument("--also", default="skewed_large", help="comma list of further workloads reported under 'also'")
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the CPU oracle's FFN sample (0 = skip)")
     ap.add_argument("--no-static", action="store_true", help="skip the static-capacity baseline runs")
+    ap.add_argument("--no-buffering", action="store_true", help="skip the expert-buffering runs")
+    ap.add_argument("--buffering-steps", type=int, default=16, help="decode steps of the expert-buffering runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write elementwise kernel three times (untimed): gives counter runs "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) a kernel of known traffic to scale by")
@@ -257,6 +332,9 @@ def main():
         static[args.config] = run_static(args.config, [1.0, 2.0])
         for name in also:
             static[name] = run_static(name, [1.0, 2.0])
+    buffering = None
+    if not args.no_buffering:
+        buffering = run_buffering("mt_decoder", [16, 48, 96], args.buffering_steps)
     cpu = cpu_baseline(args.config, main_res["host"], args.cpu_tokens) if args.cpu_tokens > 0 else None
 
     dom = dict(main_res["dominant"])
@@ -283,6 +361,7 @@ def main():
                             frac=v["frac"], traffic=v["traffic"]) for k, v in main_res["kernels"].items()},
         "also": also,
         "static_baseline": static,
+        "expert_buffering": buffering,
         "paper_context": "paper reports only relative whole-model speedups of dynamic over static gating on "
                          "8xV100 nodes (LM 6.21-11.23x, MT encoder 5.75-10.98x, MT decoder 2.58-5.71x); "
                          "no absolute number exists for this metric",
