@@ -11,7 +11,8 @@
  * on exactly their rows, and the original order is restored by indexing.  The
  * STATIC gating the paper replaces (Sec. 3.2, Sec. 5.1: fixed capacity per
  * expert, one-hot dispatch masks multiplied with the tokens, drops and zero
- * padding) is exported as a baseline for comparison.
+ * padding) is exported as a baseline for comparison.  Expert Buffering (Sec. 6:
+ * expert parameters in host memory behind a small device cache) is at the end.
  *
  * Conventions for every call
  *   - Plain C.  Returns MOE_OK (0) or a negative MOE_ERR_* code; after an error
@@ -25,8 +26,8 @@
  *     may overlap in time).
  *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
  *     the default stream) and never wait for the device or read device data on
- *     the host.  Argument errors are found on the host before anything is
- *     launched.
+ *     the host -- except moe_profile_end and moe_layer_forward_buffered, which say
+ *     so.  Argument errors are found on the host before anything is launched.
  *   - "elem" below is the storage type named by moe_config_t.dtype: float for
  *     MOE_DTYPE_F32, bfloat16 bit patterns for MOE_DTYPE_BF16.  Accumulation is
  *     always fp32; gate logits and gate weights are always fp32.
