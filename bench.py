@@ -28,15 +28,16 @@ VALU_F32_PEAK_TFLOPS = 157.3  # fp32 vector
 
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
-# 1 GiB calibration kernel: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE; see profiles/moe_layer_forward_*.txt).
+# 1 GiB calibration kernel: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE; see profiles/moe_layer_forward_*.txt; an
+# expert GEMM's figure is the sum over its two launches).
 # Counter runs cannot be made from inside this script, so the figures of the committed profiles are
 # quoted for the kernels they cover; any other (workload, kernel) reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("lm", "expert_gemm1"): 876500 * 1024, ("lm", "expert_gemm2"): 859616 * 1024,
-    ("lm", "dispatch"): 49376 * 1024, ("lm", "combine"): 49514 * 1024, ("lm", "gate_gemm"): 19592 * 1024,
-    ("skewed_large", "expert_gemm1"): 16712609 * 1024, ("skewed_large", "expert_gemm2"): 15288476 * 1024,
-    ("skewed_large", "dispatch"): 788756 * 1024, ("skewed_large", "combine"): 790982 * 1024,
-    ("skewed_large", "gate_gemm"): 299303 * 1024,
+    ("lm", "expert_gemm1"): 803668 * 1024, ("lm", "expert_gemm2"): 847058 * 1024,
+    ("lm", "dispatch"): 49376 * 1024, ("lm", "combine"): 49515 * 1024, ("lm", "gate_gemm"): 19579 * 1024,
+    ("skewed_large", "expert_gemm1"): 12354088 * 1024, ("skewed_large", "expert_gemm2"): 10914283 * 1024,
+    ("skewed_large", "dispatch"): 788765 * 1024, ("skewed_large", "combine"): 790992 * 1024,
+    ("skewed_large", "gate_gemm"): 299292 * 1024,
 }
 
 
