@@ -116,7 +116,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     // tile time.  So the launch with tail_mode 1 stops at the last whole round, and a second launch
     // (tail_mode 2, a smaller tile shape, more blocks per CU) runs the L leftover tiles as SUB
     // sub-tiles each.  Both compute the same cut from the device-side tile count; the split is taken
-    // when the sub-tiles' lower per-flop rate (about 0.69) still beats one more whole round.
+    // when the sub-tiles' lower rate still beats one more whole round (measured: a tail of L tiles
+    // costs 1.5 to 1.7 x L / G rounds, so it is taken for L < G / 1.8).
     constexpr int PT = 256;                             // parent tile edge
     constexpr int SUB_N = PT / BN > 0 ? PT / BN : 1;    // sub-tiles per parent along N
     constexpr int SUB = (PT / BM > 0 ? PT / BM : 1) * SUB_N;
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     int cut = 0;                               // first parent tile of the tail
     if (GROUPED && p.tail_mode != 0) {
         const int left = live % p.main_slots;
-        cut = (left > 0 && left * 29 < p.main_slots * 20) ? live - left : live;
+        cut = (left > 0 && left * 9 < p.main_slots * 5) ? live - left : live;
         live = tail_sub ? (live - cut) * SUB : cut;
     }
     const int chunk = (live + 7) >> 3;         // per XCD
@@ -684,10 +685,10 @@ static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *mai
     int64_t grid = (int64_t)num_cus * blocks_per_cu;
     int64_t tiles = (int64_t)m_tiles * n_tiles;
     if (p.tail_mode == 2) {
-        // max_m_tiles counts 256-row parents; at most (main_slots * 20 - 1) / 29 of the parent tiles are left over
+        // max_m_tiles counts 256-row parents; at most (main_slots * 5 - 1) / 9 of the parent tiles are left over
         p.main_slots = *main_grid;
         const int64_t parents = (int64_t)m_tiles * ceil_div(p.N, 256);
-        const int64_t left_max = ((int64_t)p.main_slots * 20 - 1) / 29;
+        const int64_t left_max = ((int64_t)p.main_slots * 5 - 1) / 9;
         tiles = (parents < left_max ? parents : left_max) * ((256 / BM) * (256 / BN));
         if (tiles <= 0) return MOE_OK;
     }

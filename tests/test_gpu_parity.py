@@ -184,6 +184,12 @@ FFN_CASES = [
     ("bf16", [64] * 16, 512, 1024, False),
     ("f32", [100, 0, 37, 64, 1], 64, 128, True),
     ("f32", [300], 128, 256, False),
+    # 256-row tiles: 24 M tiles x 13 N tiles = 312 tiles on 256 CUs -> one whole round in the main
+    # launch, 56 leftover tiles as 128x128 sub-tiles in the tail launch; the second GEMM (24 tiles)
+    # runs in the tail launch alone
+    ("bf16", [1100, 0, 900, 257, 1500, 640, 3, 700], 256, 3328, False),
+    # 24 x 17 = 408 tiles: the 152 leftover tiles are too many for the tail launch, two main rounds
+    ("bf16", [1100, 0, 900, 257, 1500, 640, 3, 700], 256, 4352, True),
 ]
 
 
