@@ -245,6 +245,8 @@ struct FfnExtra {
     const int32_t *stage_of = nullptr;
     int stage = 0;
     int64_t slot_stride = 0;
+    // the routing step has already written the tile map for M tiles of this height (0 = it has not)
+    int tile_map_ready_bm = 0;
 };
 
 // Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows, F] and the tile arrays are scratch.
@@ -260,8 +262,11 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
     const int v2 = gemm_variant(c.dtype, n_rows, c.E, c.D, h->num_cus);
     const int bm1 = gemm_variant_block_m(c.dtype, v1), bm2 = gemm_variant_block_m(c.dtype, v2);
     int max_tiles = (int)(n_rows / bm1) + c.E + 1;
-    int rc = launch_tile_map(offsets, c.E, bm1, tile_expert, tile_row, num_tiles, max_tiles, ex.stage_of, ex.stage, s);
-    if (rc != MOE_OK) return rc;
+    int rc = MOE_OK;
+    if (ex.stage_of || ex.tile_map_ready_bm != bm1) {
+        rc = launch_tile_map(offsets, c.E, bm1, tile_expert, tile_row, num_tiles, max_tiles, ex.stage_of, ex.stage, s);
+        if (rc != MOE_OK) return rc;
+    }
 
     GemmParams p;
     memset(&p, 0, sizeof(p));
@@ -663,7 +668,13 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
                                    at<int32_t>(workspace, L.block_hist), s);
     rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s);
     if (rc != MOE_OK) return rc;
-    rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, at<int32_t>(workspace, L.block_hist), s);
+    // the routing step's scan kernel also writes the first expert GEMM's tile map (not when the
+    // experts are buffered: their tile maps are per stage)
+    const int64_t n_rows = (int64_t)T * c.k;
+    const int bm1 = cache ? 0 : gemm_variant_block_m(c.dtype, gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus));
+    rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, at<int32_t>(workspace, L.block_hist), s, bm1,
+                      at<int32_t>(workspace, L.tile_expert), at<int32_t>(workspace, L.tile_row),
+                      at<int32_t>(workspace, L.num_tiles), bm1 > 0 ? (int)(n_rows / bm1) + c.E + 1 : 0);
     if (rc != MOE_OK) return rc;
     // dispatch: a scatter of its own, or folded into the first GEMM's row addressing (then Xp is never written)
     const bool fused = fused_dispatch_ok(h, T);
@@ -677,6 +688,7 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
     } else {
         FfnExtra ex;
         ex.a_rows = fused ? src_tok : nullptr;
+        ex.tile_map_ready_bm = bm1;
         rc = do_expert_ffn(h, fused ? x : xp, ex, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
     }
     if (rc != MOE_OK) return rc;

@@ -139,8 +139,9 @@ int launch_tile_map(const int32_t *offsets, int E, int block_m, int32_t *tile_ex
 int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s);
 // block_hist: scratch of route_blocks(T)*E int32
 int route_blocks(int T);
-int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets,
-                 int32_t *dst_row, int32_t *src_tok, int32_t *block_hist, hipStream_t s);
+int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,
+                 int32_t *src_tok, int32_t *block_hist, hipStream_t s, int tile_bm = 0, int32_t *tile_expert = nullptr,
+                 int32_t *tile_row = nullptr, int32_t *num_tiles = nullptr, int max_m_tiles = 0);
 
 // ---- row movement --------------------------------------------------------------------------------
 int launch_dispatch(int dtype, const void *x, const int32_t *dst_row, int T, int D, int k, void *xp,

@@ -189,9 +189,14 @@ __global__ __launch_bounds__(kThreads) void route_hist_kernel(const int32_t *__r
 
 // One block of 1024 threads.  Threads are laid out [segment][expert]: EP = E rounded up to a
 // power of two (>= 1), S = 1024 / EP segments, each covering a contiguous range of blocks.
+// tile_bm > 0: also emits the grouped GEMM's M-tile map for tiles of tile_bm rows (what
+// tile_map_kernel computes from the offsets), saving that launch in the fused layer call.
 __global__ __launch_bounds__(1024) void route_scan_kernel(int32_t *__restrict__ block_hist, int nblk, int E, int EP,
                                                           int total, int32_t *__restrict__ counts,
-                                                          int32_t *__restrict__ offsets)
+                                                          int32_t *__restrict__ offsets, int tile_bm,
+                                                          int32_t *__restrict__ tile_expert,
+                                                          int32_t *__restrict__ tile_row,
+                                                          int32_t *__restrict__ num_tiles, int max_m_tiles)
 {
     __shared__ int seg_sum[1024];
     __shared__ int wave_tot[16];
@@ -232,11 +237,35 @@ __global__ __launch_bounds__(1024) void route_scan_kernel(int32_t *__restrict__ 
     __syncthreads();
     int wbase = 0;
     for (int w2 = 0; w2 < wave; ++w2) wbase += wave_tot[w2];
+    const int my_off = wbase + incl - cnt;
     if (threadIdx.x < E) {
         counts[threadIdx.x] = cnt;
-        offsets[threadIdx.x] = wbase + incl - cnt;
+        offsets[threadIdx.x] = my_off;
     }
     if (threadIdx.x == 0) offsets[E] = total;
+    if (tile_bm > 0) {  // uniform over the block
+        const int nt = (threadIdx.x < E && cnt > 0) ? (cnt + tile_bm - 1) / tile_bm : 0;
+        int incl_t = nt;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl_t, off, kWave);
+            if (lane >= off) incl_t += up;
+        }
+        __syncthreads();  // wave_tot is reused
+        if (lane == kWave - 1) wave_tot[wave] = incl_t;
+        __syncthreads();
+        int tbase = 0;
+        for (int w2 = 0; w2 < wave; ++w2) tbase += wave_tot[w2];
+        const int first = tbase + incl_t - nt;
+        for (int i = 0; i < nt; ++i) {
+            const int ti = first + i;
+            if (ti < max_m_tiles) {
+                tile_expert[ti] = threadIdx.x;
+                tile_row[ti] = my_off + i * tile_bm;
+            }
+        }
+        if (threadIdx.x == 1023) num_tiles[0] = min(first + nt, max_m_tiles);
+    }
 }
 
 template <int KMAX>
@@ -298,7 +327,8 @@ __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__r
 }
 
 int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,
-                 int32_t *src_tok, int32_t *block_hist, hipStream_t s)
+                 int32_t *src_tok, int32_t *block_hist, hipStream_t s, int tile_bm, int32_t *tile_expert,
+                 int32_t *tile_row, int32_t *num_tiles, int max_m_tiles)
 {
     const int nblk = route_blocks(T);
     int EP = 1;
@@ -306,7 +336,8 @@ int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32
     ProfScope ps("route", s);  // histogram + scan + rank together
     hipLaunchKernelGGL(route_hist_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, block_hist);
     MOE_LAUNCH_CHECK("route_hist_kernel");
-    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, nblk, E, EP, T * k, counts, offsets);
+    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, nblk, E, EP, T * k, counts, offsets,
+                       tile_bm, tile_expert, tile_row, num_tiles, max_m_tiles);
     MOE_LAUNCH_CHECK("route_scan_kernel");
     if (T > 0) {
         // KMAX = slots a lane compares per expert: the smallest instantiation that holds k
