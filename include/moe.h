@@ -263,6 +263,27 @@ int moe_layer_forward_buffered(moe_handle_t *h, moe_expert_cache_t *cache, const
                                const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes,
                                void *stream);
 
+/* ---- Load-balancing placement (Sec. 7): which device hosts which expert ---- */
+
+/* Host logic on historical activation data; no device work.  A [E,B] host fp32, row-major:
+ * A[m*B + b] = fraction of batch b's tokens that went to expert m.  Every device gets E / n_devices
+ * experts (E must divide evenly).  Experts are taken in descending order of their average load
+ * (equal: lower id first) and put on the device that offers the smallest load (equal: lower device
+ * id); a full device leaves the candidates.
+ *   greedy (Sec. 7.1):          the load of a device is the sum of its experts' average loads;
+ *   anticorrelation (Sec. 7.2): for the current expert a, the load of a device is the sum over its
+ *                               experts m of average[m] + corr_weight * S[a][m], S the Pearson
+ *                               correlation of the two experts' activations (0 for an expert that
+ *                               never varies); the paper uses corr_weight = 0.5.
+ * device_of [E] host int32 out.  MOE_ERR_INVALID_ARG on NULL pointers or sizes that do not fit. */
+int moe_placement_greedy(const float *A, int32_t E, int32_t B, int32_t n_devices, int32_t *device_of);
+int moe_placement_anticorrelation(const float *A, int32_t E, int32_t B, int32_t n_devices, double corr_weight,
+                                  int32_t *device_of);
+/* Max Load = the largest share of a batch that any device receives, over all batches; Avg Max
+ * Load = the largest share per batch, averaged over the batches (Sec. 7.1).  Outputs may be NULL. */
+int moe_placement_loads(const float *A, int32_t E, int32_t B, const int32_t *device_of, int32_t n_devices,
+                        double *max_load, double *avg_max_load);
+
 #ifdef __cplusplus
 }
 #endif

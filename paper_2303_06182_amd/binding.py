@@ -34,6 +34,7 @@ EXPORTS = [
     "moe_cache_policy_create", "moe_cache_policy_destroy", "moe_cache_policy_reset", "moe_cache_policy_step",
     "moe_cache_policy_stats", "moe_expert_cache_bytes", "moe_expert_cache_create", "moe_expert_cache_destroy",
     "moe_expert_cache_reset", "moe_expert_cache_stats", "moe_layer_forward_buffered",
+    "moe_placement_greedy", "moe_placement_anticorrelation", "moe_placement_loads",
 ]
 
 
@@ -124,6 +125,13 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_forward_buffered.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting), vp,
                                                i64, vp]
     lib.moe_layer_forward_buffered.restype = ctypes.c_int
+    pf, pd = ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)
+    lib.moe_placement_greedy.argtypes = [pf, i32, i32, i32, pi32]
+    lib.moe_placement_greedy.restype = ctypes.c_int
+    lib.moe_placement_anticorrelation.argtypes = [pf, i32, i32, i32, ctypes.c_double, pi32]
+    lib.moe_placement_anticorrelation.restype = ctypes.c_int
+    lib.moe_placement_loads.argtypes = [pf, i32, i32, pi32, i32, pd, pd]
+    lib.moe_placement_loads.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -376,3 +384,34 @@ class ExpertCache:
                                                    _ptr(b2), T, _ptr(y), L._routing_struct(routing_out), ws, wsb,
                                                    _stream()))
         return y
+
+
+def _activation_array(A):
+    E = len(A)
+    B = len(A[0]) if E else 0
+    flat = (ctypes.c_float * (E * B))(*[float(v) for row in A for v in row])
+    return flat, E, B
+
+
+def moe_placement_greedy(A, n_devices: int):
+    """A: E rows of B activation fractions (host) -> device of every expert (Sec. 7.1)."""
+    flat, E, B = _activation_array(A)
+    out = (ctypes.c_int32 * max(E, 1))()
+    _check(load_library().moe_placement_greedy(flat, E, B, n_devices, out))
+    return list(out)[:E]
+
+
+def moe_placement_anticorrelation(A, n_devices: int, corr_weight: float = 0.5):
+    flat, E, B = _activation_array(A)
+    out = (ctypes.c_int32 * max(E, 1))()
+    _check(load_library().moe_placement_anticorrelation(flat, E, B, n_devices, corr_weight, out))
+    return list(out)[:E]
+
+
+def moe_placement_loads(A, device_of, n_devices: int):
+    """-> (Max Load, Avg Max Load) of a placement on activation data A (Sec. 7.1)."""
+    flat, E, B = _activation_array(A)
+    d = (ctypes.c_int32 * max(E, 1))(*[int(v) for v in device_of])
+    mx, av = ctypes.c_double(0), ctypes.c_double(0)
+    _check(load_library().moe_placement_loads(flat, E, B, d, n_devices, ctypes.byref(mx), ctypes.byref(av)))
+    return mx.value, av.value
