@@ -241,6 +241,20 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
         if (bias) bias += (int64_t)t.expert * p.strideBias;
         const bool vec_ok = !OUT_F32 || ((p.ldc & 3) == 0 && (p.N & 3) == 0);
+        // The fp32 offsets of this lane's columns are fetched before the first store: a load
+        // issued between stores would have to wait for every store before it (memory operations
+        // of a wave complete in order), once per group of four columns.
+        float bias32[NI][4][4];
+        if (p.bias_f32) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = t.n0 + wn * WTN + ni * 32 + 8 * g + 4 * (lane >> 5);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) bias32[ni][g][i] = (col + i < p.N) ? p.bias_f32[col + i] : 0.f;
+                }
+        }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int row = t.row0 + wm * WTM + mi * 32 + (lane & 31);
@@ -274,8 +288,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                     }
                     if (p.bias_f32) {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (col + i < p.N) v[i] += p.bias_f32[col + i];
+                        for (int i = 0; i < 4; ++i) v[i] += bias32[ni][g][i];
                     }
                     if (RELU) {
 #pragma unroll
