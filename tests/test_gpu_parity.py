@@ -396,3 +396,35 @@ def test_argument_errors(dev):
         small.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"])
     assert e.value.code == binding.MOE_ERR_WORKSPACE
     torch.cuda.synchronize()
+
+
+def test_layer_forward_can_be_captured_in_a_graph(dev):
+    """The fused call only enqueues kernels on the caller's stream (no allocation, no host wait,
+    no memset node), so it can be recorded into a HIP graph; every replay, with eager work and
+    synchronisations in between, must reproduce the eager result bit for bit."""
+    w = wl.CONFIGS["lm"].scaled(name="graph", T=1500, D=256, F=512, E=16)
+    g = cuda(wl.make_inputs(w))
+    m = layer_for(w)
+    y_eager = torch.empty((w.T, w.D), dtype=torch.bfloat16, device="cuda")
+    y_graph = torch.empty_like(y_eager)
+
+    def step(out):
+        m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"], y=out)
+
+    for _ in range(3):
+        step(y_eager)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(y_graph)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(y_graph)
+    for _ in range(4):
+        y_graph.zero_()
+        graph.replay()
+        step(y_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(y_eager, y_graph)
