@@ -289,7 +289,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="lm")
-    ap.add_argument("--also", default="skewed_large", help="comma list of further workloads reported under 'also'")
+    ap.add_argument("--also", default="skewed_large,mt_encoder,mt_decoder,tiny_f32",
+                    help="comma list of further workloads reported under 'also' (the static baseline runs only "
+                         "for the headline workload and skewed_large)")
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the CPU oracle's FFN sample (0 = skip)")
     ap.add_argument("--no-static", action="store_true", help="skip the static-capacity baseline runs")
     ap.add_argument("--no-buffering", action="store_true", help="skip the expert-buffering runs")
@@ -332,7 +334,8 @@ def main():
     if not args.no_static:
         static[args.config] = run_static(args.config, [1.0, 2.0])
         for name in also:
-            static[name] = run_static(name, [1.0, 2.0])
+            if name == "skewed_large":
+                static[name] = run_static(name, [1.0, 2.0])
     buffering = None
     if not args.no_buffering:
         buffering = run_buffering("mt_decoder", [16, 48, 96], args.buffering_steps)
