@@ -274,6 +274,12 @@ SMALL = [
     wl.CONFIGS["lm"].scaled(name="e4_k4", T=300, D=128, F=256, E=4, k=4, gate_scale=100.0, zipf_s=0.0),
     wl.CONFIGS["lm"].scaled(name="e1_k1", T=300, D=128, F=256, E=1, k=1, zipf_s=0.0),
     wl.CONFIGS["lm"].scaled(name="odd_dims", T=301, D=72, F=136, E=6, k=2, gate_scale=100.0),
+    # the limits of the configuration space: E = MOE_MAX_E, k = MOE_MAX_K, E not a multiple of 4
+    wl.CONFIGS["lm"].scaled(name="e1024_k8", T=260, D=64, F=64, E=1024, k=8, gate_scale=100.0, zipf_s=0.0),
+    wl.CONFIGS["lm"].scaled(name="e1024_k1_f32", dtype="f32", T=70, D=64, F=64, E=1024, k=1, gate_scale=100.0,
+                            zipf_s=0.0),
+    wl.CONFIGS["lm"].scaled(name="e37_k3", T=513, D=192, F=320, E=37, k=3, gate_scale=100.0),
+    wl.CONFIGS["lm"].scaled(name="e130_k2", T=257, D=128, F=128, E=130, k=2, gate_scale=100.0, zipf_s=0.0),
 ]
 
 
