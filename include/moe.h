@@ -206,6 +206,30 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
                              int32_t *dropped_count, const moe_routing_t *routing_out,
                              void *workspace, int64_t workspace_bytes, void *stream);
 
+/* ---- Weight-only 8-bit expert weights (an extension for the weight-streaming regime; not in ----
+ * ---- the paper: its decoder steps, Sec. 4, are bound by reading expert parameters)          ---- */
+
+/* W[e] ~ scale[e] * q[e]: q are OCP e4m3 bytes (1 sign, 4 exponent, 3 mantissa bits, no infinity,
+ * largest value 448), scale[e] is the smallest power of two with max|W[e]| / scale[e] <= 448 (1 for
+ * an all-zero expert), q = W / scale rounded to nearest even.  w [E, elems_per_expert] elem (device),
+ * q_out [E, elems_per_expert] bytes (device), scale_out [E] fp32 (device); elems_per_expert a
+ * multiple of 4.  Enqueued on `stream`. */
+int moe_quantize_e4m3(moe_handle_t *h, const void *w, int32_t E, int64_t elems_per_expert, void *q_out,
+                      float *scale_out, void *stream);
+
+/* moe_expert_ffn / moe_layer_forward with such weights: w1_q [E,F,D], w2_q [E,D,F] bytes, w1_scale,
+ * w2_scale [E] fp32.  Activations, biases and outputs stay elem = bf16; every e4m3 value is a bf16
+ * value, so the products are those of the dequantised weights, accumulated in fp32 and multiplied
+ * by the scale once per output.  Needs dtype bf16 and D, F multiples of 64 (MOE_ERR_UNSUPPORTED
+ * otherwise).  Halves the parameter bytes a step reads; meant for small batches per expert. */
+int moe_expert_ffn_w8(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1_q, const void *w2_q,
+                      const float *w1_scale, const float *w2_scale, const void *b1, const void *b2, int32_t n_rows,
+                      void *yp, void *workspace, int64_t workspace_bytes, void *stream);
+int moe_layer_forward_w8(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1_q,
+                         const void *w2_q, const float *w1_scale, const float *w2_scale, const void *b1,
+                         const void *b2, int32_t T, void *y, const moe_routing_t *routing_out, void *workspace,
+                         int64_t workspace_bytes, void *stream);
+
 /* ---- Expert Buffering (Sec. 6): expert parameters in host memory, a device cache of a few ----
  * ---- experts, copies overlapped with expert computation                                   ---- */
 

@@ -35,6 +35,7 @@ EXPORTS = [
     "moe_cache_policy_stats", "moe_expert_cache_bytes", "moe_expert_cache_create", "moe_expert_cache_destroy",
     "moe_expert_cache_reset", "moe_expert_cache_stats", "moe_layer_forward_buffered",
     "moe_placement_greedy", "moe_placement_anticorrelation", "moe_placement_loads",
+    "moe_quantize_e4m3", "moe_expert_ffn_w8", "moe_layer_forward_w8",
 ]
 
 
@@ -132,6 +133,13 @@ def load_library() -> ctypes.CDLL:
     lib.moe_placement_anticorrelation.restype = ctypes.c_int
     lib.moe_placement_loads.argtypes = [pf, i32, i32, pi32, i32, pd, pd]
     lib.moe_placement_loads.restype = ctypes.c_int
+    lib.moe_quantize_e4m3.argtypes = [vp, vp, i32, i64, vp, vp, vp]
+    lib.moe_quantize_e4m3.restype = ctypes.c_int
+    lib.moe_expert_ffn_w8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i64, vp]
+    lib.moe_expert_ffn_w8.restype = ctypes.c_int
+    lib.moe_layer_forward_w8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting),
+                                         vp, i64, vp]
+    lib.moe_layer_forward_w8.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -269,6 +277,33 @@ class MoeLayer:
         _check(self.lib.moe_layer_forward(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1), _ptr(w2), _ptr(b1),
                                           _ptr(b2), T, _ptr(y), self._routing_struct(routing_out), ws, wsb,
                                           _stream()))
+        return y
+
+    def moe_quantize_e4m3(self, w):
+        """w [E, ...] -> (q uint8 of the same shape, scale [E] fp32)."""
+        E = w.shape[0]
+        q = self._new(tuple(w.shape), torch.uint8)
+        scale = self._new((E,), torch.float32)
+        _check(self.lib.moe_quantize_e4m3(self.h, _ptr(w), E, w[0].numel(), _ptr(q), _ptr(scale), _stream()))
+        return q, scale
+
+    def moe_expert_ffn_w8(self, xp, offsets, w1_q, w2_q, w1_scale, w2_scale, b1=None, b2=None):
+        n_rows = xp.shape[0]
+        yp = self._new((n_rows, self.D), self.torch_dtype)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_expert_ffn_w8(self.h, _ptr(xp), _ptr(offsets), _ptr(w1_q), _ptr(w2_q), _ptr(w1_scale),
+                                          _ptr(w2_scale), _ptr(b1), _ptr(b2), n_rows, _ptr(yp), ws, wsb, _stream()))
+        return yp
+
+    def moe_layer_forward_w8(self, x, wg, w1_q, w2_q, w1_scale, w2_scale, gate_bias=None, b1=None, b2=None, y=None,
+                             routing_out=None):
+        T = x.shape[0]
+        if y is None:
+            y = self._new((T, self.D), self.torch_dtype)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_layer_forward_w8(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1_q), _ptr(w2_q),
+                                             _ptr(w1_scale), _ptr(w2_scale), _ptr(b1), _ptr(b2), T, _ptr(y),
+                                             self._routing_struct(routing_out), ws, wsb, _stream()))
         return y
 
     def moe_profile_begin(self) -> None:

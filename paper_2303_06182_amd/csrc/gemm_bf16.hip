@@ -84,13 +84,20 @@ struct TileInfo {
     int row0, row_end, expert, n0;
 };
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES>
+// B8: the B operand (the weights) is stored as 8-bit floats (OCP e4m3, one byte per element, a tile
+// row of 64 elements = 64 bytes) with one fp32 scale per expert; a fragment is widened to bf16 in
+// registers after the LDS read (every e4m3 value is a bf16 value, so the products are exact) and the
+// scale multiplies the fp32 accumulators in the epilogue.  Direct-to-LDS pipeline only.
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES,
+          bool B8 = false>
 __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams p)
 {
     constexpr int THREADS = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MI = WTM / 32, NI = WTN / 32;
-    constexpr int A_IT = BM * 8 / THREADS, B_IT = BN * 8 / THREADS;
+    constexpr int A_IT = BM * 8 / THREADS, B_IT = (B8 ? BN * 4 : BN * 8) / THREADS;
+    constexpr int BTILE = B8 ? BN * BK / 2 : BN * BK;  // one B stage in 16-bit units
+    static_assert(!B8 || (BN * 4) % THREADS == 0, "8-bit B tile rows must split evenly over threads");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
     static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "tile rows must split evenly over threads");
 
@@ -102,6 +109,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     uint16_t *sB = sA + NSTAGE * BM * BK;                   // [NSTAGE][BN*64]
     static_assert(NSTAGE >= 2, "at least two LDS stages");
     static_assert(!RSTAGE || KFULL, "the register-staged pipeline needs K to be a multiple of the K tile");
+    static_assert(!B8 || (KFULL && !RSTAGE && GROUPED), "8-bit weights: grouped direct-to-LDS pipeline, K a multiple of the K tile");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -191,16 +199,34 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     // MFMAs of one K tile out of LDS stage `cur`.
     auto compute = [&](int cur) {
         const uint16_t *cA = sA + cur * BM * BK + (wm * WTM + frag_row) * BK;
-        const uint16_t *cB = sB + cur * BN * BK + (wn * WTN + frag_row) * BK;
+        const uint16_t *cB = sB + cur * BTILE + (wn * WTN + frag_row) * (B8 ? BK / 2 : BK);
         bf16x8 af[2][MI], bfr[2][NI];
         auto load_frags = [&](int ks, int set) {
             const int chunkpos = ((ks * 2 + frag_half) ^ swz) << 3;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
                 af[set][mi] = *reinterpret_cast<const bf16x8 *>(cA + mi * 32 * BK + chunkpos);
+            if constexpr (B8) {
+                // 64-byte rows, 16-byte chunk c of row r at chunk position c ^ ((r >> 2) & 3); the 8
+                // bytes of this lane's fragment: chunk ks, half frag_half
+                const int bytepos = ((ks ^ ((lane >> 2) & 3)) << 4) + (frag_half << 3);
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(cB + ni * 32 * BK + chunkpos);
+                for (int ni = 0; ni < NI; ++ni) {
+                    const uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint8_t *>(cB) +
+                                                                       ni * 32 * (BK) + bytepos);
+                    const f32x2 f0 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.x, false);
+                    const f32x2 f1 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.x, true);
+                    const f32x2 f2 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.y, false);
+                    const f32x2 f3 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.y, true);
+                    const uint4 packed = make_uint4(pack_bf16(f0[0], f0[1]), pack_bf16(f1[0], f1[1]),
+                                                    pack_bf16(f2[0], f2[1]), pack_bf16(f3[0], f3[1]));
+                    bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(&packed);
+                }
+            } else {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(cB + ni * 32 * BK + chunkpos);
+            }
         };
         load_frags(0, 0);
 #pragma unroll
@@ -240,6 +266,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         }
         const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
         if (bias) bias += (int64_t)t.expert * p.strideBias;
+        const float b_scale = (B8 && p.b_scale) ? p.b_scale[t.expert] : 1.f;
+        (void)b_scale;
         const bool vec_ok = !OUT_F32 || ((p.ldc & 3) == 0 && (p.N & 3) == 0);
         // The fp32 offsets of this lane's columns are fetched before the first store: a load
         // issued between stores would have to wait for every store before it (memory operations
@@ -272,6 +300,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[i]) : "a"(acc[mi][ni][4 * g + i]));
                         else
                             v[i] = acc[mi][ni][4 * g + i];
+                    }
+                    if constexpr (B8) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] *= b_scale;
                     }
                     if (bias) {
                         if (col + 3 < p.N) {
@@ -333,9 +365,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         constexpr int RPI = 64 / CPRW;              // strip rows one 64-lane access covers
         if constexpr (ACC_IN_AGPR) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         uint8_t *stg = reinterpret_cast<uint8_t *>(STRIP_IN_A ? sA + free_stage * BM * BK + wave * A_IT * 8 * BK
-                                                             : sB + free_stage * BN * BK + wave * B_IT * 8 * BK);
+                                                             : sB + free_stage * BTILE + wave * B_IT * 8 * BK);
         const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
         if (bias) bias += (int64_t)t.expert * p.strideBias;
+        const float b_scale = (B8 && p.b_scale) ? p.b_scale[t.expert] : 1.f;
+        (void)b_scale;
         const int r = lane & 31;
         const int col_base = t.n0 + wn * WTN;
 #pragma unroll
@@ -353,6 +387,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[i]) : "a"(acc[mi][ni][4 * g + i]));
                         else
                             v[i] = acc[mi][ni][4 * g + i];
+                    }
+                    if constexpr (B8) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] *= b_scale;
                     }
                     if (bias && col < p.N) {  // N is a multiple of 8 for bf16 output: the 4 columns exist together
                         const uint2 bb = *reinterpret_cast<const uint2 *>(bias + col);
@@ -421,16 +459,35 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 }
                 a_off[i] = (gr - gr0) * (int)p.lda + kc * 8;
             }
+            if constexpr (B8) {
+                // one instruction = 1 KB = 16 rows of 64 bytes: lane L lands in row (L >> 2), chunk slot
+                // (L & 3) and fetches K chunk (L & 3) ^ ((row >> 2) & 3); offsets are in bytes, carried
+                // as half as many 16-bit units
+                const uint8_t *Bg8 = reinterpret_cast<const uint8_t *>(Bg0) +
+                                     (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
 #pragma unroll
-            for (int i = 0; i < B_IT; ++i) {
-                const int r = (wave * B_IT + i) * 8 + (lane >> 3);
-                const int kc = (lane & 7) ^ ((r >> 1) & 7);
-                const int gn = min(ti.n0 + r, p.N - 1);
-                if (i == 0) {
-                    gn0 = gn;
-                    b_base = Bg + (int64_t)gn * p.ldb;
+                for (int i = 0; i < B_IT; ++i) {
+                    const int r = (wave * B_IT + i) * 16 + (lane >> 2);
+                    const int kc = (lane & 3) ^ ((r >> 2) & 3);
+                    const int gn = min(ti.n0 + r, p.N - 1);
+                    if (i == 0) {
+                        gn0 = gn;
+                        b_base = reinterpret_cast<const uint16_t *>(Bg8 + (int64_t)gn * p.ldb);
+                    }
+                    b_off[i] = ((gn - gn0) * (int)p.ldb + kc * 16) / 2;  // ldb is a multiple of 64
                 }
-                b_off[i] = (gn - gn0) * p.ldb + kc * 8;
+            } else {
+#pragma unroll
+                for (int i = 0; i < B_IT; ++i) {
+                    const int r = (wave * B_IT + i) * 8 + (lane >> 3);
+                    const int kc = (lane & 7) ^ ((r >> 1) & 7);
+                    const int gn = min(ti.n0 + r, p.N - 1);
+                    if (i == 0) {
+                        gn0 = gn;
+                        b_base = Bg + (int64_t)gn * p.ldb;
+                    }
+                    b_off[i] = (gn - gn0) * p.ldb + kc * 8;
+                }
             }
         };
         auto issue = [&](int kt, int buf) {
@@ -440,8 +497,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                                  (lds_void *)(sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < B_IT; ++i)
-                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * BK)),
-                                                 (lds_void *)(sB + buf * BN * BK + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * (B8 ? BK / 2 : BK))),
+                                                 (lds_void *)(sB + buf * BTILE + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
         };
         // The loads run STAGES-1 K tiles ahead of the MFMAs along the block's whole sequence of
         // (tile, K tile) pairs, so the pipeline never drains between tiles and an epilogue's stores
@@ -485,7 +542,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             };
             auto lds_put = [&](int buf, int i, const uint4 &v) {
                 uint16_t *d = i < A_IT ? sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK
-                                       : sB + buf * BN * BK + (wave * B_IT + (i - A_IT)) * 8 * BK;
+                                       : sB + buf * BTILE + (wave * B_IT + (i - A_IT)) * 8 * BK;
                 *reinterpret_cast<uint4 *>(d + lane * 8) = v;
             };
             auto advance = [&]() {
@@ -508,7 +565,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                                                    chunkpos);
                 else
                     bfr[set][m - MI] = *reinterpret_cast<const bf16x8 *>(
-                        sB + buf * BN * BK + (wn * WTN + frag_row + (m - MI) * 32) * BK + chunkpos);
+                        sB + buf * BTILE + (wn * WTN + frag_row + (m - MI) * 32) * BK + chunkpos);
             };
             // the ds_writes of this iteration must be complete before anyone reads the buffer
             auto rs_sync = [&]() {
@@ -677,15 +734,16 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES>
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES,
+          bool B8 = false>
 static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *main_grid)
 {
     GemmParams p = p_in;
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + BN) * BK * sizeof(uint16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES>;
+    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (B8 ? BN / 2 : BN)) * BK * sizeof(uint16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES, B8>;
     static int blocks_per_cu = 0;  // per instantiation
     if (blocks_per_cu == 0) {
         MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -726,6 +784,14 @@ static int launch_one(const GemmParams &p, int num_cus, hipStream_t s, int *main
                : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB, 2>(p, num_cus, s, main_grid);
 }
 
+// grouped GEMM with 8-bit weights (K a multiple of the K tile: checked by the caller)
+template <int BM, int BN, int WM, int WN, int MINB, int STAGES>
+static int launch_grouped_w8(const GemmParams &p, bool relu, int num_cus, hipStream_t s)
+{
+    return relu ? launch_k<BM, BN, WM, WN, false, true, true, true, MINB, STAGES, true>(p, num_cus, s, nullptr)
+                : launch_k<BM, BN, WM, WN, false, false, true, true, MINB, STAGES, true>(p, num_cus, s, nullptr);
+}
+
 // Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves, pipeline)
 //   8: 256x256, 8 waves, register-staged    10: 128x128, 4 waves, register-staged
 //   5: 256x256, 8 waves, direct-to-LDS       1: 128x128, 4 waves, direct-to-LDS
@@ -757,12 +823,20 @@ static bool no_tail_split()
 // every grouped bf16 shape reads A through per-lane row pointers when K is a multiple of the K tile
 bool gemm_bf16_variant_gathers(int variant, int K) { return variant != 0 && K % BK == 0; }
 
+// 8-bit weights are for the weight-streaming regime: always the small tiles (three / four LDS
+// stages deep, the stages cost half the LDS), whatever the row count
+int gemm_bf16_variant_w8(int64_t n_rows, int E)
+{
+    const int64_t avg = E > 0 ? n_rows / E : n_rows;
+    return avg >= 48 ? 22 : 23;
+}
+
 int gemm_bf16_variant_block_m(int v)
 {
     switch (v) {
     case 1: case 10: return 128;
-    case 2: return 64;
-    case 3: return 32;
+    case 2: case 22: return 64;
+    case 3: case 23: return 32;
     default: return 256;
     }
 }
@@ -831,6 +905,8 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
     case 10: return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(p, relu, num_cus, s);
     case 5: return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
     case 1: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
+    case 22: return launch_grouped_w8<64, 128, 1, 4, 2, 3>(p, relu, num_cus, s);
+    case 23: return launch_grouped_w8<32, 128, 1, 4, 2, 4>(p, relu, num_cus, s);
     case 2: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
     case 3: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
     default:

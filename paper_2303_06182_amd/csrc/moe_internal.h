@@ -98,6 +98,7 @@ struct GemmParams {
     int64_t ldb;
     int64_t strideB;     // elements between experts (between slots with b_slot)
     const int32_t *b_slot;  // grouped: expert e's weights are slot b_slot[e] of B (NULL = e)
+    const float *b_scale;   // 8-bit weight variants: fp32 scale per expert (NULL = 1)
     const void *bias;    // elem [N] / [E,N], or NULL
     int64_t strideBias;
     const float *bias_f32;  // fp32 [N] or NULL (gate offsets)
@@ -129,6 +130,10 @@ bool gemm_variant_gathers(int dtype, int variant);
 // max(.,0) before the store.
 int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool out_f32, bool relu,
                 int num_cus, hipStream_t s);
+
+// 8-bit weights (quant.hip): q [E, per_expert] e4m3 bytes and scale [E] from w [E, per_expert] (dtype elem);
+// per_expert a multiple of 4.
+int launch_quantize_e4m3(int dtype, const void *w, int E, int64_t per_expert, uint8_t *q, float *scale, hipStream_t s);
 
 // Tile map for the grouped GEMM from the device-side offsets (one block).
 // stage_of != NULL: only the experts e with stage_of[e] == stage get tiles.

@@ -1,0 +1,210 @@
+"""GPU parity of the weight-only 8-bit (e4m3) expert-weight path, through the C-ABI:
+the quantiser byte for byte against the CPU oracle, and the expert FFN / the whole layer against
+the fp64 oracle fed the dequantised weights (scale * q is exactly a bf16 number, so the two sides
+see identical operands and the bar is the bf16 path's)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as orc
+from oracle import quant_e4m3 as oq
+from paper_2303_06182_amd import binding, workloads as wl
+from helpers import TOL, guarded_inputs, norm_max_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load_library()
+    return torch.device("cuda:0")
+
+
+def dequant_bf16(q: np.ndarray, s: np.ndarray) -> torch.Tensor:
+    d = oq.dequantize(q, s)
+    t = torch.from_numpy(d.astype(np.float32)).to(torch.bfloat16)
+    assert np.array_equal(t.float().numpy().astype(np.float64), d), "scale * q must be exact in bf16"
+    return t
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_quantizer_bytes_and_scales_equal_the_oracle(dev, dtype):
+    say("quantizer", dtype)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    E, F, D = 7, 96, 72
+    w = wl.normal(21, 0, (E, F, D), 1.0, tdt)
+    mul = torch.tensor([1e-3, 0.02, 1.0, 30.0, 0.0, 1.0, 1.0]).reshape(E, 1, 1)
+    w = (w.float() * mul).to(tdt)
+    w[5].clamp_(-1.75, 1.75)
+    w[5, 0, 0] = 1.75            # absmax exactly 448 * 2^-8: the scale must not grow
+    w[6, 3, 5] = -7.0            # absmax exactly 448 * 2^-6, negative
+    # ties and subnormals of the grid at scale 2^-6: midpoints between neighbouring codes
+    grid = oq.code_values()[:0x7F] * 2.0 ** -6
+    mid = torch.from_numpy(((grid[:-1] + grid[1:]) / 2).astype(np.float32))
+    w[6].view(-1)[10:10 + mid.numel()] = mid.to(tdt)
+    m = binding.MoeLayer(8, 64, 64, E, 1, dtype)
+    q, s = m.moe_quantize_e4m3(w.cuda())
+    torch.cuda.synchronize()
+    rq, rs = oq.quantize(w.float().numpy().astype(np.float64))
+    np.testing.assert_array_equal(to_np(s), rs)
+    got = to_np(q)
+    # +0 and -0 are one number: the hardware keeps the sign of a value that rounds to zero
+    same = (got == rq) | (((got | rq) & 0x7F) == 0)
+    assert same.all(), int((~same).sum())
+
+
+W8_FFN_CASES = [
+    # counts per expert (ragged, with empty experts), D, F, bias
+    ([130, 0, 257, 1, 64, 0, 33, 515], 256, 512, False),
+    ([5, 0, 0, 1, 2, 0, 3, 0, 0, 1, 1, 0], 128, 192, True),
+    ([16] * 32, 512, 1024, True),                 # few rows per expert: the 32-row variant
+    ([64, 48, 100, 47, 70, 90], 192, 320, False),  # around the variant threshold
+    ([700, 45], 64, 64, True),
+]
+
+
+@pytest.mark.parametrize("case", W8_FFN_CASES, ids=[str(i) for i in range(len(W8_FFN_CASES))])
+def test_expert_ffn_w8_parity(dev, case):
+    counts, D, F, bias = case
+    say("w8 ffn case", case)
+    E, N = len(counts), int(sum(counts))
+    tdt = torch.bfloat16
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    xp = wl.normal(31, 0, (N, D), 1.0, tdt)
+    w1 = wl.normal(31, 1, (E, F, D), 1.0 / np.sqrt(D), tdt)
+    w2 = wl.normal(31, 2, (E, D, F), 1.0 / np.sqrt(F), tdt)
+    w1[0] *= 37.0                                   # experts with different scales
+    w2[E - 1] *= 1.0 / 64
+    b1 = wl.normal(31, 3, (E, F), 0.5, tdt) if bias else None
+    b2 = wl.normal(31, 4, (E, D), 0.5, tdt) if bias else None
+    m = binding.MoeLayer(N, D, F, E, 1, "bf16")
+    q1, s1 = m.moe_quantize_e4m3(w1.cuda())
+    q2, s2 = m.moe_quantize_e4m3(w2.cuda())
+    # idle experts are poisoned with the NaN code: their weights must never reach a result
+    for e, c in enumerate(counts):
+        if c == 0:
+            q1[e] = 0x7F
+            q2[e] = 0x7F
+    yp = m.moe_expert_ffn_w8(xp.cuda(), torch.from_numpy(offsets).cuda(), q1, q2, s1, s2,
+                             None if b1 is None else b1.cuda(), None if b2 is None else b2.cuda())
+    torch.cuda.synchronize()
+    rq1, rs1 = oq.quantize(w1.float().numpy().astype(np.float64))
+    rq2, rs2 = oq.quantize(w2.float().numpy().astype(np.float64))
+    ref = orc.expert_ffn(xp, offsets, dequant_bf16(rq1, rs1), dequant_bf16(rq2, rs2), b1, b2)
+    got = to_np(yp)
+    assert np.all(np.isfinite(got))
+    err = norm_max_err(got, ref)
+    say("  w8 ffn err", err)
+    assert err <= TOL["bf16"], err
+
+
+W8_LAYER = [
+    wl.CONFIGS["mt_decoder"].scaled(name="w8_dec", D=256, F=512),
+    wl.CONFIGS["lm"].scaled(name="w8_lm", T=1000, D=256, F=512),
+    wl.CONFIGS["lm"].scaled(name="w8_e37_k3", T=513, D=192, F=320, E=37, k=3, gate_scale=100.0),
+]
+
+
+def run_w8_layer(w, device="cpu", check_experts=None):
+    inp, _ = guarded_inputs(w, device=device, with_ffn_bias=True)
+    g = {k: (None if v is None else v.cuda()) for k, v in inp.items()}
+    host = {k: (None if v is None else v.cpu()) for k, v in inp.items() if k not in ("w1", "w2")}
+    m = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, "bf16")
+    q1, s1 = m.moe_quantize_e4m3(g["w1"])
+    q2, s2 = m.moe_quantize_e4m3(g["w2"])
+    r = m.empty_routing(w.T)
+    y = m.moe_layer_forward_w8(g["x"], g["wg"], q1, q2, s1, s2, g["gate_bias"], g["b1"], g["b2"], routing_out=r)
+    torch.cuda.synchronize()
+    logits = orc.gate_logits(host["x"], host["wg"], host["gate_bias"])
+    ridx, rw = orc.topk(logits, w.k, True)
+    np.testing.assert_array_equal(to_np(r["topk_idx"]), ridx)
+    rc, ro, rd, rs = orc.route(ridx, w.E)
+    np.testing.assert_array_equal(to_np(r["dst_row"]), rd)
+    np.testing.assert_array_equal(to_np(r["offsets"]), ro)
+    # Reference weights: the oracle's own quantisation of the experts in check_experts (all, by
+    # default), which must equal the library's bytes; for the others in use, the library's bytes
+    # (the quantiser has its own byte-for-byte test) dequantised by the oracle.  Idle experts
+    # stay zero: the oracle never reads them.
+    active = [e for e in range(w.E) if rc[e] > 0]
+    own = set(active if check_experts is None else [e for e in active if e in check_experts])
+    d1 = torch.zeros((w.E, w.F, w.D), dtype=torch.bfloat16)
+    d2 = torch.zeros((w.E, w.D, w.F), dtype=torch.bfloat16)
+    hs1, hs2 = to_np(s1), to_np(s2)
+    for e in active:
+        for wt, q, hs, d in ((g["w1"], q1, hs1, d1), (g["w2"], q2, hs2, d2)):
+            qe = to_np(q[e:e + 1])
+            if e in own:
+                rq, rsc = oq.quantize(wt[e:e + 1].float().cpu().numpy().astype(np.float64))
+                assert rsc[0] == hs[e]
+                assert ((qe == rq) | (((qe | rq) & 0x7F) == 0)).all()
+                qe = rq
+            d[e] = dequant_bf16(qe, hs[e:e + 1])[0]
+    ref = orc.layer_tokens(host["x"], d1, d2, ridx, rw, b1=host["b1"], b2=host["b2"])
+    got = to_np(y)
+    assert np.all(np.isfinite(got))
+    err = norm_max_err(got, ref)
+    say("  %s: active experts=%d err=%.3e" % (w.name, len(active), err))
+    assert err <= TOL["bf16"], err
+    return y, g, (q1, q2, s1, s2)
+
+
+@pytest.mark.parametrize("w", W8_LAYER, ids=[w.name for w in W8_LAYER])
+def test_layer_forward_w8_small(dev, w):
+    say("w8 layer", w)
+    run_w8_layer(w)
+
+
+def test_layer_forward_w8_equals_stagewise_calls_and_is_close_to_bf16_weights(dev):
+    w = wl.CONFIGS["mt_decoder"].scaled(name="w8_stage", D=256, F=512)
+    y, g, (q1, q2, s1, s2) = run_w8_layer(w)
+    m = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, "bf16")
+    _, idx, tw = m.moe_gate_topk(g["x"], g["wg"], g["gate_bias"])
+    counts, offsets, dst_row, src_tok = m.moe_route_counts(idx)
+    xp = m.moe_dispatch(g["x"], dst_row)
+    yp = m.moe_expert_ffn_w8(xp, offsets, q1, q2, s1, s2, g["b1"], g["b2"])
+    y2 = m.moe_combine(yp, dst_row, tw)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    # against the unquantised layer: the weight rounding error (<= 2^-4 per weight, random sign)
+    y16 = m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"], g["b1"], g["b2"])
+    torch.cuda.synchronize()
+    rel = norm_max_err(to_np(y), to_np(y16))
+    say("  w8 vs bf16 weights: normalised max difference %.3e" % rel)
+    assert rel < 0.15
+
+
+def test_layer_forward_w8_full_size_decoder(dev):
+    w = wl.CONFIGS["mt_decoder"]
+    say("w8 full", w)
+    run_w8_layer(w, device="cuda", check_experts={0, 1, 2, 3, 64, 127})
+    torch.cuda.empty_cache()
+
+
+def test_w8_argument_errors(dev):
+    m = binding.MoeLayer(64, 72, 128, 4, 2, "bf16")      # D not a multiple of 64
+    x = torch.zeros(8, 72, dtype=torch.bfloat16, device="cuda")
+    wg = torch.zeros(4, 72, dtype=torch.bfloat16, device="cuda")
+    q1 = torch.zeros(4, 128, 72, dtype=torch.uint8, device="cuda")
+    q2 = torch.zeros(4, 72, 128, dtype=torch.uint8, device="cuda")
+    s = torch.ones(4, device="cuda")
+    with pytest.raises(binding.MoeError) as ei:
+        m.moe_layer_forward_w8(x, wg, q1, q2, s, s)
+    assert ei.value.code == binding.MOE_ERR_UNSUPPORTED
+    m32 = binding.MoeLayer(64, 64, 128, 4, 2, "f32")
+    with pytest.raises(binding.MoeError) as ei:
+        m32.moe_expert_ffn_w8(torch.zeros(8, 64, device="cuda"), torch.zeros(5, dtype=torch.int32, device="cuda"),
+                              q1, q2, s, s)
+    assert ei.value.code == binding.MOE_ERR_UNSUPPORTED
+    ok = binding.MoeLayer(64, 64, 128, 4, 2, "bf16")
+    with pytest.raises(binding.MoeError) as ei:
+        binding._check(ok.lib.moe_quantize_e4m3(ok.h, None, 4, 64, None, None, None))
+    assert ei.value.code == binding.MOE_ERR_INVALID_ARG
+    torch.cuda.synchronize()
