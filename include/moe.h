@@ -211,14 +211,18 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
 
 /* W[e] ~ scale[e] * q[e]: q are OCP e4m3 bytes (1 sign, 4 exponent, 3 mantissa bits, no infinity,
  * largest value 448), scale[e] is the smallest power of two with max|W[e]| / scale[e] <= 448 (1 for
- * an all-zero expert), q = W / scale rounded to nearest even.  w [E, elems_per_expert] elem (device),
- * q_out [E, elems_per_expert] bytes (device), scale_out [E] fp32 (device); elems_per_expert a
- * multiple of 4.  Enqueued on `stream`. */
-int moe_quantize_e4m3(moe_handle_t *h, const void *w, int32_t E, int64_t elems_per_expert, void *q_out,
+ * an all-zero expert), q = W / scale rounded to nearest even.
+ * w [E, rows, cols] elem (device), scale_out [E] fp32 (device), q_out E * rows * cols bytes (device)
+ * in a blocked layout made for the grouped GEMM's loads: inside expert e, the byte of element
+ * (n, k) sits at  ((n / 16) * (cols / 64) + k / 64) * 1024 + (n % 16) * 64 + k % 64,  i.e. 16 rows
+ * x 64 columns form one contiguous 1 KB block and the blocks of a 16-row group follow each other
+ * along the columns.  rows a multiple of 16, cols a multiple of 64 (MOE_ERR_INVALID_ARG otherwise).
+ * Enqueued on `stream`. */
+int moe_quantize_e4m3(moe_handle_t *h, const void *w, int32_t E, int32_t rows, int32_t cols, void *q_out,
                       float *scale_out, void *stream);
 
-/* moe_expert_ffn / moe_layer_forward with such weights: w1_q [E,F,D], w2_q [E,D,F] bytes, w1_scale,
- * w2_scale [E] fp32.  Activations, biases and outputs stay elem = bf16; every e4m3 value is a bf16
+/* moe_expert_ffn / moe_layer_forward with such weights: w1_q (from W1 [E,F,D]: rows = F, cols = D)
+ * and w2_q (from W2 [E,D,F]: rows = D, cols = F) in the layout above, w1_scale, w2_scale [E] fp32.  Activations, biases and outputs stay elem = bf16; every e4m3 value is a bf16
  * value, so the products are those of the dequantised weights, accumulated in fp32 and multiplied
  * by the scale once per output.  Needs dtype bf16 and D, F multiples of 64 (MOE_ERR_UNSUPPORTED
  * otherwise).  Halves the parameter bytes a step reads; meant for small batches per expert. */

@@ -10,6 +10,10 @@ library's kernels.  Only tests, the smoke check and the benchmark's baseline leg
     scale(W)    the smallest power of two s with max|W| <= 448 s (1 for an all-zero W)
     quantize    q = the e4m3 value nearest to W / s, ties to the even mantissa, as a byte
     dequantize  s * value(q)
+
+The library hands its bytes out in a blocked order (16 rows x 64 columns per contiguous 1 KB, the
+blocks of a 16-row group one after the other along the columns); ``blocked`` / ``unblocked``
+restate that order with numpy reshapes so that tests can compare bytes element by element.
 """
 from __future__ import annotations
 
@@ -84,3 +88,17 @@ def dequantize(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
     vals = code_values()[np.asarray(q, dtype=np.uint8)]
     shape = (len(scale),) + (1,) * (vals.ndim - 1)
     return vals * np.asarray(scale, dtype=np.float64).reshape(shape)
+
+
+def blocked(q: np.ndarray) -> np.ndarray:
+    """[E, rows, cols] bytes -> [E, rows * cols] in the library's order: element (n, k) at
+    ((n // 16) * (cols // 64) + k // 64) * 1024 + (n % 16) * 64 + k % 64."""
+    E, rows, cols = q.shape
+    assert rows % 16 == 0 and cols % 64 == 0
+    return q.reshape(E, rows // 16, 16, cols // 64, 64).transpose(0, 1, 3, 2, 4).reshape(E, rows * cols)
+
+
+def unblocked(qb: np.ndarray, rows: int, cols: int) -> np.ndarray:
+    """Inverse of ``blocked``: [E, rows * cols] -> [E, rows, cols]."""
+    E = qb.shape[0]
+    return qb.reshape(E, rows // 16, cols // 64, 16, 64).transpose(0, 1, 3, 2, 4).reshape(E, rows, cols)

@@ -133,7 +133,7 @@ def load_library() -> ctypes.CDLL:
     lib.moe_placement_anticorrelation.restype = ctypes.c_int
     lib.moe_placement_loads.argtypes = [pf, i32, i32, pi32, i32, pd, pd]
     lib.moe_placement_loads.restype = ctypes.c_int
-    lib.moe_quantize_e4m3.argtypes = [vp, vp, i32, i64, vp, vp, vp]
+    lib.moe_quantize_e4m3.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     lib.moe_quantize_e4m3.restype = ctypes.c_int
     lib.moe_expert_ffn_w8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i64, vp]
     lib.moe_expert_ffn_w8.restype = ctypes.c_int
@@ -280,11 +280,11 @@ class MoeLayer:
         return y
 
     def moe_quantize_e4m3(self, w):
-        """w [E, ...] -> (q uint8 of the same shape, scale [E] fp32)."""
-        E = w.shape[0]
-        q = self._new(tuple(w.shape), torch.uint8)
+        """w [E, rows, cols] -> (q uint8 [E, rows * cols] in the library's blocked layout, scale [E] fp32)."""
+        E, rows, cols = w.shape
+        q = self._new((E, rows * cols), torch.uint8)
         scale = self._new((E,), torch.float32)
-        _check(self.lib.moe_quantize_e4m3(self.h, _ptr(w), E, w[0].numel(), _ptr(q), _ptr(scale), _stream()))
+        _check(self.lib.moe_quantize_e4m3(self.h, _ptr(w), E, rows, cols, _ptr(q), _ptr(scale), _stream()))
         return q, scale
 
     def moe_expert_ffn_w8(self, xp, offsets, w1_q, w2_q, w1_scale, w2_scale, b1=None, b2=None):

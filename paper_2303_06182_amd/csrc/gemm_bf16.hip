@@ -461,20 +461,24 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             }
             if constexpr (B8) {
                 // one instruction = 1 KB = 16 rows of 64 bytes: lane L lands in row (L >> 2), chunk slot
-                // (L & 3) and fetches K chunk (L & 3) ^ ((row >> 2) & 3); offsets are in bytes, carried
-                // as half as many 16-bit units
+                // (L & 3) and fetches K chunk (L & 3) ^ ((row >> 2) & 3).  In memory that 1 KB block is
+                // contiguous and the blocks of a 16-row group follow each other along K (the
+                // quantiser's layout), so the offsets are those of the group; they are in bytes,
+                // carried as half as many 16-bit units.
                 const uint8_t *Bg8 = reinterpret_cast<const uint8_t *>(Bg0) +
                                      (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
+                const int group_bytes = (K / BK) * 1024;  // one 16-row group over the whole of K
+                const int last_group = p.N / 16 - 1;       // groups past the end repeat the last one
 #pragma unroll
                 for (int i = 0; i < B_IT; ++i) {
                     const int r = (wave * B_IT + i) * 16 + (lane >> 2);
                     const int kc = (lane & 3) ^ ((r >> 2) & 3);
-                    const int gn = min(ti.n0 + r, p.N - 1);
+                    const int grp = min((ti.n0 + r) >> 4, last_group);
                     if (i == 0) {
-                        gn0 = gn;
-                        b_base = reinterpret_cast<const uint16_t *>(Bg8 + (int64_t)gn * p.ldb);
+                        gn0 = grp;
+                        b_base = reinterpret_cast<const uint16_t *>(Bg8 + (int64_t)grp * group_bytes);
                     }
-                    b_off[i] = ((gn - gn0) * (int)p.ldb + kc * 16) / 2;  // ldb is a multiple of 64
+                    b_off[i] = ((grp - gn0) * group_bytes + (r & 15) * 64 + kc * 16) / 2;
                 }
             } else {
 #pragma unroll
@@ -497,7 +501,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                                  (lds_void *)(sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < B_IT; ++i)
-                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * (B8 ? BK / 2 : BK))),
+                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * (B8 ? 512 : BK))),
                                                  (lds_void *)(sB + buf * BTILE + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
         };
         // The loads run STAGES-1 K tiles ahead of the MFMAs along the block's whole sequence of
@@ -824,9 +828,18 @@ static bool no_tail_split()
 bool gemm_bf16_variant_gathers(int variant, int K) { return variant != 0 && K % BK == 0; }
 
 // 8-bit weights are for the weight-streaming regime: always the small tiles (three / four LDS
-// stages deep, the stages cost half the LDS), whatever the row count
+// stages deep, the stages cost half the LDS), whatever the row count.  (Measured on 128 experts of
+// 2048 x 8192 with 1 to 64 rows each: 2 to 6 stages, 32x64 and 32x256 tiles and up to 6 blocks per
+// CU all land within +-8 % of these two; deeper pipelines lose blocks per CU and are slower.)
 int gemm_bf16_variant_w8(int64_t n_rows, int E)
 {
+    static int forced = -1;
+    if (forced < 0) {
+        const char *e = getenv("MOE355_W8_VARIANT");  // tuning override, 0 / unset = automatic
+        forced = e ? atoi(e) : 0;
+        if (forced != 22 && forced != 23) forced = 0;
+    }
+    if (forced) return forced;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
     return avg >= 48 ? 22 : 23;
 }

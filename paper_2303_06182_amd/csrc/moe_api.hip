@@ -730,7 +730,7 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
 }
 
 // ---- 8-bit expert weights -----------------------------------------------------------------------
-int moe_quantize_e4m3(moe_handle_t *h, const void *w, int32_t E, int64_t elems_per_expert, void *q_out,
+int moe_quantize_e4m3(moe_handle_t *h, const void *w, int32_t E, int32_t rows, int32_t cols, void *q_out,
                       float *scale_out, void *stream)
 {
     g_err[0] = 0;
@@ -738,13 +738,13 @@ int moe_quantize_e4m3(moe_handle_t *h, const void *w, int32_t E, int64_t elems_p
         set_error("handle is NULL");
         return MOE_ERR_INVALID_ARG;
     }
-    if (E < 1 || E > 65535 || elems_per_expert < 4 || elems_per_expert % 4 != 0) {
-        set_error("quantize: E = %d outside [1, 65535] or elems_per_expert = %lld not a positive multiple of 4", E,
-                  (long long)elems_per_expert);
+    if (E < 1 || E > 65535 || rows < 16 || rows % 16 != 0 || cols < 64 || cols % 64 != 0) {
+        set_error("quantize: E = %d outside [1, 65535], rows = %d not a positive multiple of 16 or cols = %d not a "
+                  "positive multiple of 64", E, rows, cols);
         return MOE_ERR_INVALID_ARG;
     }
     if (bad_ptr(w, "w") || bad_ptr(q_out, "q_out") || bad_ptr(scale_out, "scale_out")) return MOE_ERR_INVALID_ARG;
-    return launch_quantize_e4m3(h->cfg.dtype, w, E, elems_per_expert, static_cast<uint8_t *>(q_out), scale_out,
+    return launch_quantize_e4m3(h->cfg.dtype, w, E, rows, cols, static_cast<uint8_t *>(q_out), scale_out,
                                 (hipStream_t)stream);
 }
 

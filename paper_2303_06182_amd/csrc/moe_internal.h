@@ -133,7 +133,8 @@ int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool 
 
 // 8-bit weights (quant.hip): q [E, per_expert] e4m3 bytes and scale [E] from w [E, per_expert] (dtype elem);
 // per_expert a multiple of 4.
-int launch_quantize_e4m3(int dtype, const void *w, int E, int64_t per_expert, uint8_t *q, float *scale, hipStream_t s);
+int launch_quantize_e4m3(int dtype, const void *w, int E, int rows, int cols, uint8_t *q, float *scale,
+                         hipStream_t s);
 
 // Tile map for the grouped GEMM from the device-side offsets (one block).
 // stage_of != NULL: only the experts e with stage_of[e] == stage get tiles.

@@ -2,6 +2,13 @@
 // as OCP e4m3 bytes with one power-of-two fp32 scale per expert, W[e] ~ scale[e] * q[e].  The scale
 // is the smallest power of two s with max|W[e]| / s <= 448 (the largest e4m3 value), so the division
 // is exact and nothing saturates; the rounding to e4m3 is the hardware's round-to-nearest-even.
+//
+// Byte layout of q: not row-major.  The grouped GEMM moves 16 weight rows x 64 K-bytes with one
+// load instruction, so exactly that 1 KB block is contiguous, and the blocks of one 16-row group
+// follow each other along K:  byte of element (n, k) of a [rows, cols] matrix =
+//     ((n / 16) * (cols / 64) + k / 64) * 1024 + (n % 16) * 64 + k % 64.
+// A GEMM block then reads a few strictly sequential streams instead of 64-byte slices of rows
+// that lie `cols` bytes apart.
 #include "moe_internal.h"
 
 namespace moe355 {
@@ -42,13 +49,14 @@ __device__ __forceinline__ float scale_of(float absmax)
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(kQThreads) void quantize_kernel(const void *__restrict__ w, int64_t per_expert,
+__global__ __launch_bounds__(kQThreads) void quantize_kernel(const void *__restrict__ w, int64_t per_expert, int cols,
                                                              const uint32_t *__restrict__ absmax_bits,
                                                              uint8_t *__restrict__ q)
 {
     const int e = blockIdx.y;
     const float inv = 1.f / scale_of(__uint_as_float(absmax_bits[e]));  // a power of two: exact
-    // four elements (one 32-bit word of output) per thread and step; per_expert is a multiple of 4
+    const int kblocks = cols >> 6;
+    // four elements of one row (one 32-bit word of output) per thread and step; cols is a multiple of 64
     for (int64_t i = ((int64_t)blockIdx.x * kQThreads + threadIdx.x) * 4; i < per_expert;
          i += (int64_t)gridDim.x * kQThreads * 4) {
         const int64_t g = (int64_t)e * per_expert + i;
@@ -56,7 +64,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_kernel(const void *__restr
         const float c = load_elem<BF16>(w, g + 2) * inv, d = load_elem<BF16>(w, g + 3) * inv;
         int word = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
         word = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, word, true);
-        *reinterpret_cast<int *>(q + g) = word;
+        const int64_t n = i / cols;
+        const int k = (int)(i - n * cols);
+        const int64_t tiled = ((n >> 4) * kblocks + (k >> 6)) * 1024 + (n & 15) * 64 + (k & 63);
+        *reinterpret_cast<int *>(q + (int64_t)e * per_expert + tiled) = word;
     }
 }
 
@@ -66,8 +77,9 @@ __global__ void finish_scale_kernel(uint32_t *__restrict__ bits_then_scale, int 
     if (e < E) bits_then_scale[e] = __float_as_uint(scale_of(__uint_as_float(bits_then_scale[e])));
 }
 
-int launch_quantize_e4m3(int dtype, const void *w, int E, int64_t per_expert, uint8_t *q, float *scale, hipStream_t s)
+int launch_quantize_e4m3(int dtype, const void *w, int E, int rows, int cols, uint8_t *q, float *scale, hipStream_t s)
 {
+    const int64_t per_expert = (int64_t)rows * cols;
     uint32_t *bits = reinterpret_cast<uint32_t *>(scale);
     int rc = launch_fill_u32(bits, E, 0u, s);
     if (rc != MOE_OK) return rc;
@@ -77,10 +89,10 @@ int launch_quantize_e4m3(int dtype, const void *w, int E, int64_t per_expert, ui
     const dim3 grid((unsigned)bx, (unsigned)E);
     if (dtype == MOE_DTYPE_BF16) {
         hipLaunchKernelGGL(absmax_kernel<true>, grid, dim3(kQThreads), 0, s, w, per_expert, bits);
-        hipLaunchKernelGGL(quantize_kernel<true>, grid, dim3(kQThreads), 0, s, w, per_expert, bits, q);
+        hipLaunchKernelGGL(quantize_kernel<true>, grid, dim3(kQThreads), 0, s, w, per_expert, cols, bits, q);
     } else {
         hipLaunchKernelGGL(absmax_kernel<false>, grid, dim3(kQThreads), 0, s, w, per_expert, bits);
-        hipLaunchKernelGGL(quantize_kernel<false>, grid, dim3(kQThreads), 0, s, w, per_expert, bits, q);
+        hipLaunchKernelGGL(quantize_kernel<false>, grid, dim3(kQThreads), 0, s, w, per_expert, cols, bits, q);
     }
     hipLaunchKernelGGL(finish_scale_kernel, dim3(ceil_div(E, 256)), dim3(256), 0, s, bits, E);
     MOE_LAUNCH_CHECK("quantize_e4m3");

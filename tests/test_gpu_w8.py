@@ -39,7 +39,7 @@ def dequant_bf16(q: np.ndarray, s: np.ndarray) -> torch.Tensor:
 def test_quantizer_bytes_and_scales_equal_the_oracle(dev, dtype):
     say("quantizer", dtype)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
-    E, F, D = 7, 96, 72
+    E, F, D = 7, 96, 128
     w = wl.normal(21, 0, (E, F, D), 1.0, tdt)
     mul = torch.tensor([1e-3, 0.02, 1.0, 30.0, 0.0, 1.0, 1.0]).reshape(E, 1, 1)
     w = (w.float() * mul).to(tdt)
@@ -55,7 +55,7 @@ def test_quantizer_bytes_and_scales_equal_the_oracle(dev, dtype):
     torch.cuda.synchronize()
     rq, rs = oq.quantize(w.float().numpy().astype(np.float64))
     np.testing.assert_array_equal(to_np(s), rs)
-    got = to_np(q)
+    got = oq.unblocked(to_np(q), F, D)
     # +0 and -0 are one number: the hardware keeps the sign of a value that rounds to zero
     same = (got == rq) | (((got | rq) & 0x7F) == 0)
     assert same.all(), int((~same).sum())
@@ -93,6 +93,7 @@ def test_expert_ffn_w8_parity(dev, case):
         if c == 0:
             q1[e] = 0x7F
             q2[e] = 0x7F
+    np.testing.assert_array_equal(to_np(s1), oq.quantize(w1.float().numpy().astype(np.float64))[1])
     yp = m.moe_expert_ffn_w8(xp.cuda(), torch.from_numpy(offsets).cuda(), q1, q2, s1, s2,
                              None if b1 is None else b1.cuda(), None if b2 is None else b2.cuda())
     torch.cuda.synchronize()
@@ -140,7 +141,7 @@ def run_w8_layer(w, device="cpu", check_experts=None):
     hs1, hs2 = to_np(s1), to_np(s2)
     for e in active:
         for wt, q, hs, d in ((g["w1"], q1, hs1, d1), (g["w2"], q2, hs2, d2)):
-            qe = to_np(q[e:e + 1])
+            qe = oq.unblocked(to_np(q[e:e + 1]), wt.shape[1], wt.shape[2])
             if e in own:
                 rq, rsc = oq.quantize(wt[e:e + 1].float().cpu().numpy().astype(np.float64))
                 assert rsc[0] == hs[e]
@@ -192,8 +193,8 @@ def test_w8_argument_errors(dev):
     m = binding.MoeLayer(64, 72, 128, 4, 2, "bf16")      # D not a multiple of 64
     x = torch.zeros(8, 72, dtype=torch.bfloat16, device="cuda")
     wg = torch.zeros(4, 72, dtype=torch.bfloat16, device="cuda")
-    q1 = torch.zeros(4, 128, 72, dtype=torch.uint8, device="cuda")
-    q2 = torch.zeros(4, 72, 128, dtype=torch.uint8, device="cuda")
+    q1 = torch.zeros(4, 128 * 72, dtype=torch.uint8, device="cuda")
+    q2 = torch.zeros(4, 72 * 128, dtype=torch.uint8, device="cuda")
     s = torch.ones(4, device="cuda")
     with pytest.raises(binding.MoeError) as ei:
         m.moe_layer_forward_w8(x, wg, q1, q2, s, s)
@@ -205,6 +206,9 @@ def test_w8_argument_errors(dev):
     assert ei.value.code == binding.MOE_ERR_UNSUPPORTED
     ok = binding.MoeLayer(64, 64, 128, 4, 2, "bf16")
     with pytest.raises(binding.MoeError) as ei:
-        binding._check(ok.lib.moe_quantize_e4m3(ok.h, None, 4, 64, None, None, None))
+        binding._check(ok.lib.moe_quantize_e4m3(ok.h, None, 4, 64, 64, None, None, None))
+    assert ei.value.code == binding.MOE_ERR_INVALID_ARG
+    with pytest.raises(binding.MoeError) as ei:        # cols not a multiple of 64
+        ok.moe_quantize_e4m3(torch.zeros(4, 64, 72, dtype=torch.bfloat16, device="cuda"))
     assert ei.value.code == binding.MOE_ERR_INVALID_ARG
     torch.cuda.synchronize()

@@ -86,3 +86,14 @@ def test_quantize_roundtrip_error_bound_and_fixed_points():
     # values already on the grid come back unchanged
     q2, s2 = oq.quantize(back[:4])
     assert np.array_equal(oq.dequantize(q2, s2), back[:4])
+
+
+def test_blocked_order_is_the_stated_formula_and_invertible():
+    rng = np.random.default_rng(3)
+    E, rows, cols = 3, 48, 192
+    q = rng.integers(0, 256, (E, rows, cols), dtype=np.uint8)
+    b = oq.blocked(q)
+    for _ in range(2000):
+        e, n, k = rng.integers(E), rng.integers(rows), rng.integers(cols)
+        assert b[e, ((n // 16) * (cols // 64) + k // 64) * 1024 + (n % 16) * 64 + k % 64] == q[e, n, k]
+    assert np.array_equal(oq.unblocked(b, rows, cols), q)
