@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -29,10 +30,37 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# The MFMA GEMM kernels sit at the register limit (256 accumulators + staging registers): a harmless
+# looking edit can tip one of them into scratch spills and cost 10-20 % with no other symptom, so the
+# compiler's per-kernel resource report is read and a spill there fails the build.
+NO_SPILL_SOURCES = {"gemm_bf16.hip"}
+
+
+def spilled_kernels(report: str):
+    """(kernel name, spilled VGPRs) for every kernel of a -Rpass-analysis=kernel-resource-usage
+    report that spills."""
+    out = []
+    for block in report.split("Function Name: ")[1:]:
+        name = block.split("\n", 1)[0].strip()
+        m = re.search(r"VGPRs Spill: (\d+)", block)
+        if m and int(m.group(1)) > 0:
+            out.append((name, int(m.group(1))))
+    return out
+
+
 def _compile(src: str, verbose: bool) -> str:
     obj = os.path.join(OBJDIR, src.replace(".hip", ".o"))
     cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    check = src in NO_SPILL_SOURCES
+    if check:
+        cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)
+    if check:
+        bad = spilled_kernels(r.stderr)
+        if r.returncode == 0 and bad:
+            raise RuntimeError("register spills in %s: %s" % (src, ", ".join("%s (%d VGPRs)" % b for b in bad)))
+        r.stderr = "\n".join(l for l in r.stderr.splitlines()
+                              if "remark:" not in l and not re.match(r"^\s*\d*\s*\|", l))
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))

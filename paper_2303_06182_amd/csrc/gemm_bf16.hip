@@ -134,7 +134,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     const int m_tiles = GROUPED ? p.num_tiles[0] : (p.M + BM - 1) / BM;
     int live = m_tiles * n_tiles;              // logical tiles
     int cut = 0;                               // first parent tile of the tail
-    if (GROUPED && p.tail_mode != 0) {
+    if (GROUPED && (p.tail_mode == 1 || p.tail_mode == 2)) {
         const int left = live % p.main_slots;
         cut = (left > 0 && left * 9 < p.main_slots * 5) ? live - left : live;
         live = tail_sub ? (live - cut) * SUB : cut;
@@ -621,17 +621,42 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             for (int i = 0; i < LPS; ++i) R[i] = gload(i);
             advance();
             rs_sync();
+            // A wave whose rows all lie past the end of the expert's batch (the upper half of a last
+            // tile with at most half its rows) only keeps up its share of the loads and barriers: the
+            // matrix unit of its SIMD is left to the wave that has rows.  Such a tile measured about
+            // 13 % shorter.  (Drawing tiles from a per-XCD atomic counter, so that blocks with short
+            // tiles take more of them, was tried on top: its few extra live values tipped this
+            // kernel into scratch spills, and with short tiles this little cheaper it cannot pay.)
+            auto idle_rs = [&](int cur) {
+                const int nxt = cur ^ 1;
+#pragma unroll
+                for (int i = 0; i < LPS; ++i) {
+                    lds_put(nxt, i, R[i]);
+                    R[i] = gload(i);
+                }
+                advance();
+                rs_sync();
+            };
+            const int wm_s = __builtin_amdgcn_readfirstlane(wm);
             int cur = 0;
             while (true) {
-                zero_acc();
-                for (int kt = 0; kt < KT; ++kt) {
-                    compute_rs(cur);
-                    cur ^= 1;
+                const bool idle = GROUPED && WM > 1 && t.row0 + wm_s * WTM >= t.row_end;
+                if (idle) {
+                    for (int kt = 0; kt < KT; ++kt) {
+                        idle_rs(cur);
+                        cur ^= 1;
+                    }
+                } else {
+                    zero_acc();
+                    for (int kt = 0; kt < KT; ++kt) {
+                        compute_rs(cur);
+                        cur ^= 1;
+                    }
+                    if constexpr (LDS_EPILOGUE)
+                        epilogue_lds(t, cur ^ 1);  // the buffer the last K tile was read from
+                    else
+                        epilogue(t);
                 }
-                if constexpr (LDS_EPILOGUE)
-                    epilogue_lds(t, cur ^ 1);  // the buffer the last K tile was read from
-                else
-                    epilogue(t);
                 seq += slots;
                 if (!seq_ok(seq)) break;
                 t = tile_info(seq);
@@ -906,6 +931,11 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
     switch (variant) {
     case 8: {
         // whole rounds as 256x256 tiles, the partly filled last round as 128x128 sub-tiles
+        if (getenv("MOE355_DBG_IDLE")) {
+            GemmParams q = p;
+            q.tail_mode = 77;
+            return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(q, relu, num_cus, s);
+        }
         if (p.K % BK != 0 || no_tail_split()) return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
         GemmParams q = p;
         int main_grid = 0;

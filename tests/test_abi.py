@@ -80,3 +80,16 @@ def test_null_handle_and_null_out(lib):
     assert lib.moe_create(ctypes.byref(cfg), None) == binding.MOE_ERR_INVALID_ARG
     assert lib.moe_combine(None, None, None, None, 0, None, None) == binding.MOE_ERR_INVALID_ARG
     assert lib.moe_destroy(None) == binding.MOE_OK
+
+
+def test_build_reads_register_spills_from_the_compiler_report():
+    """The build refuses GEMM kernels that spill registers; this checks its reading of the report."""
+    from paper_2303_06182_amd import build
+    line = "x.hip:94:1: remark:     %s [-Rpass-analysis=kernel-resource-usage]\n"
+    report = ("x.hip:94:1: remark: Function Name: kernel_a [-Rpass-analysis=kernel-resource-usage]\n"
+              + line % "VGPRs: 254" + line % "SGPRs Spill: 0" + line % "VGPRs Spill: 0"
+              + "x.hip:94:1: remark: Function Name: kernel_b [-Rpass-analysis=kernel-resource-usage]\n"
+              + line % "VGPRs: 256" + line % "VGPRs Spill: 119")
+    bad = build.spilled_kernels(report)
+    assert len(bad) == 1 and bad[0][0].startswith("kernel_b") and bad[0][1] == 119
+    assert build.spilled_kernels("") == []
