@@ -931,11 +931,6 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
     switch (variant) {
     case 8: {
         // whole rounds as 256x256 tiles, the partly filled last round as 128x128 sub-tiles
-        if (getenv("MOE355_DBG_IDLE")) {
-            GemmParams q = p;
-            q.tail_mode = 77;
-            return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(q, relu, num_cus, s);
-        }
         if (p.K % BK != 0 || no_tail_split()) return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
         GemmParams q = p;
         int main_grid = 0;
