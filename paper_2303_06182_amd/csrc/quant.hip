@@ -15,11 +15,23 @@ namespace moe355 {
 
 static constexpr int kQThreads = 256;
 
+// Four consecutive elements as floats: one 8-byte (bf16) or 16-byte (fp32) load.  i is a multiple of 4.
 template <bool BF16>
-__device__ __forceinline__ float load_elem(const void *w, int64_t i)
+__device__ __forceinline__ void load4(const void *w, int64_t i, float (&v)[4])
 {
-    if (BF16) return __uint_as_float((uint32_t)static_cast<const uint16_t *>(w)[i] << 16);
-    return static_cast<const float *>(w)[i];
+    if (BF16) {
+        const uint2 r = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(w) + i);
+        v[0] = __uint_as_float(r.x << 16);
+        v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16);
+        v[3] = __uint_as_float(r.y & 0xffff0000u);
+    } else {
+        const float4 r = *reinterpret_cast<const float4 *>(static_cast<const float *>(w) + i);
+        v[0] = r.x;
+        v[1] = r.y;
+        v[2] = r.z;
+        v[3] = r.w;
+    }
 }
 
 // scale[e] <- bit pattern of max |w| over the expert (non-negative floats order like their bits)
@@ -29,8 +41,12 @@ __global__ __launch_bounds__(kQThreads) void absmax_kernel(const void *__restric
 {
     const int e = blockIdx.y;
     float m = 0.f;
-    for (int64_t i = (int64_t)blockIdx.x * kQThreads + threadIdx.x; i < per_expert; i += (int64_t)gridDim.x * kQThreads)
-        m = fmaxf(m, fabsf(load_elem<BF16>(w, (int64_t)e * per_expert + i)));
+    for (int64_t i = ((int64_t)blockIdx.x * kQThreads + threadIdx.x) * 4; i < per_expert;
+         i += (int64_t)gridDim.x * kQThreads * 4) {
+        float v[4];
+        load4<BF16>(w, (int64_t)e * per_expert + i, v);
+        m = fmaxf(fmaxf(m, fmaxf(fabsf(v[0]), fabsf(v[1]))), fmaxf(fabsf(v[2]), fabsf(v[3])));
+    }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
     if ((threadIdx.x & 63) == 0) atomicMax(&absmax_bits[e], __float_as_uint(m));
@@ -60,10 +76,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_kernel(const void *__restr
     for (int64_t i = ((int64_t)blockIdx.x * kQThreads + threadIdx.x) * 4; i < per_expert;
          i += (int64_t)gridDim.x * kQThreads * 4) {
         const int64_t g = (int64_t)e * per_expert + i;
-        const float a = load_elem<BF16>(w, g) * inv, b = load_elem<BF16>(w, g + 1) * inv;
-        const float c = load_elem<BF16>(w, g + 2) * inv, d = load_elem<BF16>(w, g + 3) * inv;
-        int word = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
-        word = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, word, true);
+        float v[4];
+        load4<BF16>(w, g, v);
+        int word = __builtin_amdgcn_cvt_pk_fp8_f32(v[0] * inv, v[1] * inv, 0, false);
+        word = __builtin_amdgcn_cvt_pk_fp8_f32(v[2] * inv, v[3] * inv, word, true);
         const int64_t n = i / cols;
         const int k = (int)(i - n * cols);
         const int64_t tiled = ((n >> 4) * kblocks + (k >> 6)) * 1024 + (n & 15) * 64 + (k & 63);
