@@ -326,6 +326,130 @@ __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__r
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Small batches (decoder steps: a few hundred assignments): the three kernels above are then all
+// launch latency, so one block of 1024 threads does the whole job in LDS -- histogram, scan,
+// tile map and ranks -- with one thread per assignment a = t*k + j, in chunks of 1024.  The rank
+// of a inside its expert is (assignments of that expert in earlier chunks and waves) + (lanes
+// below it in its wave with the same expert); waves add their counts to the running per-expert
+// totals one after the other, so the order is that of a, as in the kernels above.
+// ------------------------------------------------------------------------------------------------
+static constexpr int kSmallRouteMax = 4096;  // assignments
+
+__global__ __launch_bounds__(1024) void route_small_kernel(const int32_t *__restrict__ idx, int n_assign, int E, int k,
+                                                           int32_t *__restrict__ counts,
+                                                           int32_t *__restrict__ offsets,
+                                                           int32_t *__restrict__ dst_row,
+                                                           int32_t *__restrict__ src_tok, int tile_bm,
+                                                           int32_t *__restrict__ tile_expert,
+                                                           int32_t *__restrict__ tile_row,
+                                                           int32_t *__restrict__ num_tiles, int max_m_tiles)
+{
+    __shared__ int hist[MOE_MAX_E];   // counts, then the running totals of the ranking pass
+    __shared__ int start[MOE_MAX_E];  // first row of every expert
+    __shared__ int wave_tot[16];
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    for (int e = threadIdx.x; e < MOE_MAX_E; e += 1024) hist[e] = 0;
+    __syncthreads();
+    for (int a = threadIdx.x; a < n_assign; a += 1024) atomicAdd(&hist[clamp_expert(idx[a], E)], 1);
+    __syncthreads();
+    // exclusive scan over the experts: thread e owns expert e (E <= 1024)
+    const int cnt = threadIdx.x < E ? hist[threadIdx.x] : 0;
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    int wbase = 0;
+    for (int w2 = 0; w2 < wave; ++w2) wbase += wave_tot[w2];
+    const int my_off = wbase + incl - cnt;
+    if (threadIdx.x < E) {
+        counts[threadIdx.x] = cnt;
+        offsets[threadIdx.x] = my_off;
+        start[threadIdx.x] = my_off;
+    }
+    if (threadIdx.x == 0) offsets[E] = n_assign;
+    if (tile_bm > 0) {  // uniform over the block: the grouped GEMM's M-tile map, as in route_scan_kernel
+        const int nt = (threadIdx.x < E && cnt > 0) ? (cnt + tile_bm - 1) / tile_bm : 0;
+        int incl_t = nt;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl_t, off, kWave);
+            if (lane >= off) incl_t += up;
+        }
+        __syncthreads();  // wave_tot is reused
+        if (lane == kWave - 1) wave_tot[wave] = incl_t;
+        __syncthreads();
+        int tbase = 0;
+        for (int w2 = 0; w2 < wave; ++w2) tbase += wave_tot[w2];
+        const int first = tbase + incl_t - nt;
+        for (int i = 0; i < nt; ++i) {
+            const int ti = first + i;
+            if (ti < max_m_tiles) {
+                tile_expert[ti] = threadIdx.x;
+                tile_row[ti] = my_off + i * tile_bm;
+            }
+        }
+        if (threadIdx.x == 1023) num_tiles[0] = min(first + nt, max_m_tiles);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < MOE_MAX_E; e += 1024) hist[e] = 0;  // now: assignments ranked so far
+    __syncthreads();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+    for (int a0 = 0; a0 < n_assign; a0 += 1024) {  // trip count uniform over the block
+        const int a = a0 + threadIdx.x;
+        const bool live = a < n_assign;
+        const int e = live ? clamp_expert(idx[a], E) : -1;
+        // lanes of the wave with the same expert: one ballot per distinct expert present
+        int below = 0, same = 0, leader = 0;
+        uint64_t todo = __ballot(live);
+        while (todo) {
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            const int e0 = __shfl(e, src, kWave);
+            const uint64_t mask = __ballot(e == e0);
+            if (e == e0) {
+                below = __popcll(mask & lt_mask);
+                same = __popcll(mask);
+                leader = (lane == src);
+            }
+            todo &= ~mask;
+        }
+        // the waves take their turns in order; the first lane of every expert group moves the total
+        int base = 0;
+        const int live_waves = min(16, (n_assign - a0 + kWave - 1) / kWave);  // uniform over the block
+        for (int w2 = 0; w2 < live_waves; ++w2) {
+            if (wave == w2 && live && leader) {
+                base = hist[e];
+                hist[e] = base + same;
+            }
+            __syncthreads();
+        }
+        // hand the group's base to its other lanes
+        {
+            uint64_t todo2 = __ballot(live);
+            int got = base;
+            while (todo2) {
+                const int src = __ffsll((unsigned long long)todo2) - 1;
+                const int e0 = __shfl(e, src, kWave);
+                const int b0 = __shfl(base, src, kWave);
+                const uint64_t mask = __ballot(e == e0);
+                if (e == e0) got = b0;
+                todo2 &= ~mask;
+            }
+            base = got;
+        }
+        if (live) {
+            const int r = start[e] + base + below;
+            dst_row[a] = r;
+            src_tok[r] = a / k;
+        }
+    }
+}
+
 int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,
                  int32_t *src_tok, int32_t *block_hist, hipStream_t s, int tile_bm, int32_t *tile_expert,
                  int32_t *tile_row, int32_t *num_tiles, int max_m_tiles)
@@ -334,6 +458,12 @@ int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32
     int EP = 1;
     while (EP < E) EP <<= 1;
     ProfScope ps("route", s);  // histogram + scan + rank together
+    if ((int64_t)T * k <= kSmallRouteMax) {
+        hipLaunchKernelGGL(route_small_kernel, dim3(1), dim3(1024), 0, s, idx, T * k, E, k, counts, offsets, dst_row,
+                           src_tok, tile_bm, tile_expert, tile_row, num_tiles, max_m_tiles);
+        MOE_LAUNCH_CHECK("route_small_kernel");
+        return MOE_OK;
+    }
     hipLaunchKernelGGL(route_hist_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, block_hist);
     MOE_LAUNCH_CHECK("route_hist_kernel");
     hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, nblk, E, EP, T * k, counts, offsets,
