@@ -118,7 +118,9 @@ def random_idx(T, E, k, seed, skew=False):
 
 ROUTE_CASES = [(1, 4, 2, False), (64, 128, 2, False), (255, 8, 2, False), (256, 8, 2, True), (257, 16, 1, False),
                (1000, 128, 2, True), (5000, 64, 2, True), (777, 1000, 8, False), (4096, 3, 3, False),
-               (3000, 1, 1, False), (20000, 128, 2, True)]
+               (3000, 1, 1, False), (20000, 128, 2, True),
+               # around the limit of the single-block kernel for small batches (4096 assignments)
+               (2048, 16, 2, True), (2049, 16, 2, False), (512, 1000, 8, False), (130, 1024, 8, False)]
 
 
 @pytest.mark.parametrize("T,E,k,skew", ROUTE_CASES)
