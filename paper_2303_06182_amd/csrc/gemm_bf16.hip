@@ -621,42 +621,20 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             for (int i = 0; i < LPS; ++i) R[i] = gload(i);
             advance();
             rs_sync();
-            // A wave whose rows all lie past the end of the expert's batch (the upper half of a last
-            // tile with at most half its rows) only keeps up its share of the loads and barriers: the
-            // matrix unit of its SIMD is left to the wave that has rows.  Such a tile measured about
-            // 13 % shorter.  (Drawing tiles from a per-XCD atomic counter, so that blocks with short
-            // tiles take more of them, was tried on top: its few extra live values tipped this
-            // kernel into scratch spills, and with short tiles this little cheaper it cannot pay.)
-            auto idle_rs = [&](int cur) {
-                const int nxt = cur ^ 1;
-#pragma unroll
-                for (int i = 0; i < LPS; ++i) {
-                    lds_put(nxt, i, R[i]);
-                    R[i] = gload(i);
-                }
-                advance();
-                rs_sync();
-            };
-            const int wm_s = __builtin_amdgcn_readfirstlane(wm);
+            // (Letting the waves whose rows all lie past the end of an expert's batch skip their MFMAs
+            // makes such a tile 13 % shorter, but the CUs of an XCD then drift apart, share less of the
+            // weight panels in L2, and the launch fetches 45 % more from HBM: slower overall.)
             int cur = 0;
             while (true) {
-                const bool idle = GROUPED && WM > 1 && t.row0 + wm_s * WTM >= t.row_end;
-                if (idle) {
-                    for (int kt = 0; kt < KT; ++kt) {
-                        idle_rs(cur);
-                        cur ^= 1;
-                    }
-                } else {
-                    zero_acc();
-                    for (int kt = 0; kt < KT; ++kt) {
-                        compute_rs(cur);
-                        cur ^= 1;
-                    }
-                    if constexpr (LDS_EPILOGUE)
-                        epilogue_lds(t, cur ^ 1);  // the buffer the last K tile was read from
-                    else
-                        epilogue(t);
+                zero_acc();
+                for (int kt = 0; kt < KT; ++kt) {
+                    compute_rs(cur);
+                    cur ^= 1;
                 }
+                if constexpr (LDS_EPILOGUE)
+                    epilogue_lds(t, cur ^ 1);  // the buffer the last K tile was read from
+                else
+                    epilogue(t);
                 seq += slots;
                 if (!seq_ok(seq)) break;
                 t = tile_info(seq);
