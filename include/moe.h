@@ -234,6 +234,40 @@ int moe_layer_forward_w8(moe_handle_t *h, const void *x, const void *wg, const f
                          const void *b2, int32_t T, void *y, const moe_routing_t *routing_out, void *workspace,
                          int64_t workspace_bytes, void *stream);
 
+/* ---- Weight-only 4-bit expert weights with block scales (the OCP microscaling layout; an ----
+ * ---- extension like the 8-bit one above, not in the paper)                               ---- */
+
+/* Every 32 consecutive elements of a weight row share one scale: W[n][32 b + i] ~ s[n][b] * v[n][32 b + i].
+ * v are e2m1 codes (4 bits: bit 3 sign, bits 2..0 -> 0, 0.5, 1, 1.5, 2, 3, 4, 6); s[n][b] is the
+ * smallest power of two with max|block| <= 6 s (nothing saturates), stored as the byte e with
+ * s = 2^(e - 127), e >= 1, e = 127 for an all-zero block; v = W / s rounded to nearest, ties to the
+ * even code.
+ * w [E, rows, cols] elem (device).  q_out: E * rows * cols / 2 bytes (device); inside expert e the
+ * element (n, k) is nibble (k % 2) (low nibble first) of byte
+ *   ((n / 32) * (cols / 64) + k / 64) * 1024 + (n % 32) * 32 + (k % 64) / 2,
+ * i.e. 32 rows x 64 columns form one contiguous 1 KB block and the blocks of a 32-row group follow
+ * each other along the columns.  scale_out: E * moe_mxfp4_scale_bytes(rows, cols) bytes (device);
+ * inside expert e the scale of (n, block b) is byte
+ *   ((n / 32) * ceil(cols / 512) + b / 16) * 512 + (n % 32) * 16 + b % 16
+ * (bytes of blocks past the last column are padding and unspecified).
+ * rows a multiple of 32, cols a multiple of 64 (MOE_ERR_INVALID_ARG otherwise).  Enqueued on `stream`. */
+int64_t moe_mxfp4_scale_bytes(int32_t rows, int32_t cols);
+int moe_quantize_mxfp4(moe_handle_t *h, const void *w, int32_t E, int32_t rows, int32_t cols, void *q_out,
+                       void *scale_out, void *stream);
+
+/* moe_expert_ffn / moe_layer_forward with such weights (w1_q, w1_scale from W1 [E,F,D]: rows = F,
+ * cols = D; w2_q, w2_scale from W2 [E,D,F]: rows = D, cols = F).  s * v is exactly a bf16 number, so
+ * the products are those of the dequantised weights, accumulated in fp32.  Activations, biases and
+ * outputs stay bf16.  Needs dtype bf16 and D, F multiples of 64 (MOE_ERR_UNSUPPORTED otherwise).
+ * A quarter of the parameter bytes of bf16 weights per step. */
+int moe_expert_ffn_w4(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1_q, const void *w2_q,
+                      const void *w1_scale, const void *w2_scale, const void *b1, const void *b2, int32_t n_rows,
+                      void *yp, void *workspace, int64_t workspace_bytes, void *stream);
+int moe_layer_forward_w4(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1_q,
+                         const void *w2_q, const void *w1_scale, const void *w2_scale, const void *b1,
+                         const void *b2, int32_t T, void *y, const moe_routing_t *routing_out, void *workspace,
+                         int64_t workspace_bytes, void *stream);
+
 /* ---- Expert Buffering (Sec. 6): expert parameters in host memory, a device cache of a few ----
  * ---- experts, copies overlapped with expert computation                                   ---- */
 

@@ -36,6 +36,7 @@ EXPORTS = [
     "moe_expert_cache_reset", "moe_expert_cache_stats", "moe_layer_forward_buffered",
     "moe_placement_greedy", "moe_placement_anticorrelation", "moe_placement_loads",
     "moe_quantize_e4m3", "moe_expert_ffn_w8", "moe_layer_forward_w8",
+    "moe_mxfp4_scale_bytes", "moe_quantize_mxfp4", "moe_expert_ffn_w4", "moe_layer_forward_w4",
 ]
 
 
@@ -140,6 +141,15 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_forward_w8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting),
                                          vp, i64, vp]
     lib.moe_layer_forward_w8.restype = ctypes.c_int
+    lib.moe_mxfp4_scale_bytes.argtypes = [i32, i32]
+    lib.moe_mxfp4_scale_bytes.restype = i64
+    lib.moe_quantize_mxfp4.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.moe_quantize_mxfp4.restype = ctypes.c_int
+    lib.moe_expert_ffn_w4.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i64, vp]
+    lib.moe_expert_ffn_w4.restype = ctypes.c_int
+    lib.moe_layer_forward_w4.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting),
+                                         vp, i64, vp]
+    lib.moe_layer_forward_w4.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -302,6 +312,37 @@ class MoeLayer:
             y = self._new((T, self.D), self.torch_dtype)
         ws, wsb = self._ws()
         _check(self.lib.moe_layer_forward_w8(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1_q), _ptr(w2_q),
+                                             _ptr(w1_scale), _ptr(w2_scale), _ptr(b1), _ptr(b2), T, _ptr(y),
+                                             self._routing_struct(routing_out), ws, wsb, _stream()))
+        return y
+
+    def moe_quantize_mxfp4(self, w):
+        """w [E, rows, cols] -> (q uint8 [E, rows * cols / 2], scale bytes uint8 [E, moe_mxfp4_scale_bytes]),
+        both in the library's blocked layouts."""
+        E, rows, cols = w.shape
+        nb = int(self.lib.moe_mxfp4_scale_bytes(rows, cols))
+        if nb < 0:
+            _check(nb)
+        q = self._new((E, rows * cols // 2), torch.uint8)
+        scale = torch.full((E, nb), 127, dtype=torch.uint8, device=self.device)
+        _check(self.lib.moe_quantize_mxfp4(self.h, _ptr(w), E, rows, cols, _ptr(q), _ptr(scale), _stream()))
+        return q, scale
+
+    def moe_expert_ffn_w4(self, xp, offsets, w1_q, w2_q, w1_scale, w2_scale, b1=None, b2=None):
+        n_rows = xp.shape[0]
+        yp = self._new((n_rows, self.D), self.torch_dtype)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_expert_ffn_w4(self.h, _ptr(xp), _ptr(offsets), _ptr(w1_q), _ptr(w2_q), _ptr(w1_scale),
+                                          _ptr(w2_scale), _ptr(b1), _ptr(b2), n_rows, _ptr(yp), ws, wsb, _stream()))
+        return yp
+
+    def moe_layer_forward_w4(self, x, wg, w1_q, w2_q, w1_scale, w2_scale, gate_bias=None, b1=None, b2=None, y=None,
+                             routing_out=None):
+        T = x.shape[0]
+        if y is None:
+            y = self._new((T, self.D), self.torch_dtype)
+        ws, wsb = self._ws()
+        _check(self.lib.moe_layer_forward_w4(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1_q), _ptr(w2_q),
                                              _ptr(w1_scale), _ptr(w2_scale), _ptr(b1), _ptr(b2), T, _ptr(y),
                                              self._routing_struct(routing_out), ws, wsb, _stream()))
         return y

@@ -84,20 +84,27 @@ struct TileInfo {
     int row0, row_end, expert, n0;
 };
 
-// B8: the B operand (the weights) is stored as 8-bit floats (OCP e4m3, one byte per element, a tile
-// row of 64 elements = 64 bytes) with one fp32 scale per expert; a fragment is widened to bf16 in
-// registers after the LDS read (every e4m3 value is a bf16 value, so the products are exact) and the
-// scale multiplies the fp32 accumulators in the epilogue.  Direct-to-LDS pipeline only.
+// BQ: storage of the B operand (the weights).  0: bf16.  8: 8-bit floats (OCP e4m3, one byte per
+// element, a tile row of 64 elements = 64 bytes) with one fp32 scale per expert; a fragment is
+// widened to bf16 in registers after the LDS read (every e4m3 value is a bf16 value, so the products
+// are exact) and the scale multiplies the fp32 accumulators in the epilogue.  4: 4-bit floats (OCP
+// e2m1, two per byte, a tile row = 32 bytes) with one power-of-two scale byte (e8m0) per 32
+// elements along K; the scale is applied while widening (v_cvt_scalef32_pk_bf16_fp4), the result is
+// again exactly a bf16 value.  8 and 4: direct-to-LDS pipeline only.
 template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES,
-          bool B8 = false>
+          int BQ = 0>
 __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams p)
 {
     constexpr int THREADS = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MI = WTM / 32, NI = WTN / 32;
-    constexpr int A_IT = BM * 8 / THREADS, B_IT = (B8 ? BN * 4 : BN * 8) / THREADS;
-    constexpr int BTILE = B8 ? BN * BK / 2 : BN * BK;  // one B stage in 16-bit units
+    constexpr bool B8 = BQ == 8, B4 = BQ == 4;
+    static_assert(BQ == 0 || B8 || B4, "B storage: bf16, e4m3 or e2m1");
+    constexpr int A_IT = BM * 8 / THREADS, B_IT = (B8 ? BN * 4 : B4 ? BN * 2 : BN * 8) / THREADS;
+    constexpr int BROW = B8 ? BK / 2 : B4 ? BK / 4 : BK;  // one B tile row in 16-bit units
+    constexpr int BTILE = BN * BROW;                       // one B stage in 16-bit units
     static_assert(!B8 || (BN * 4) % THREADS == 0, "8-bit B tile rows must split evenly over threads");
+    static_assert(!B4 || (BN * 2) % THREADS == 0, "4-bit B tile rows must split evenly over threads");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
     static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "tile rows must split evenly over threads");
 
@@ -109,7 +116,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     uint16_t *sB = sA + NSTAGE * BM * BK;                   // [NSTAGE][BN*64]
     static_assert(NSTAGE >= 2, "at least two LDS stages");
     static_assert(!RSTAGE || KFULL, "the register-staged pipeline needs K to be a multiple of the K tile");
-    static_assert(!B8 || (KFULL && !RSTAGE && GROUPED), "8-bit weights: grouped direct-to-LDS pipeline, K a multiple of the K tile");
+    static_assert(BQ == 0 || (KFULL && !RSTAGE && GROUPED), "8- and 4-bit weights: grouped direct-to-LDS pipeline, K a multiple of the K tile");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -197,9 +204,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     const int swz = (lane >> 1) & 7;  // == (row >> 1) & 7 for every row this lane reads
 
     // MFMAs of one K tile out of LDS stage `cur`.
-    auto compute = [&](int cur) {
+    // 4-bit weights: the scale bytes of this lane's NI weight rows for 8 consecutive K tiles (16 bytes:
+    // two 32-element blocks per K tile), for the K tiles being computed and for the 8 after them
+    uint4 sc_cur[B4 ? NI : 1], sc_nxt[B4 ? NI : 1];
+    auto compute = [&](int cur, int kt) {
         const uint16_t *cA = sA + cur * BM * BK + (wm * WTM + frag_row) * BK;
-        const uint16_t *cB = sB + cur * BTILE + (wn * WTN + frag_row) * (B8 ? BK / 2 : BK);
+        const uint16_t *cB = sB + cur * BTILE + (wn * WTN + frag_row) * BROW;
+        (void)kt;
         bf16x8 af[2][MI], bfr[2][NI];
         auto load_frags = [&](int ks, int set) {
             const int chunkpos = ((ks * 2 + frag_half) ^ swz) << 3;
@@ -220,6 +231,29 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                     const f32x2 f3 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.y, true);
                     const uint4 packed = make_uint4(pack_bf16(f0[0], f0[1]), pack_bf16(f1[0], f1[1]),
                                                     pack_bf16(f2[0], f2[1]), pack_bf16(f3[0], f3[1]));
+                    bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(&packed);
+                }
+            } else if constexpr (B4) {
+                // 32-byte rows; this lane's 8 elements of K-step ks are the 4 bytes at ks*8 + half*4, their
+                // block scale is byte (kt mod 8)*2 + ks/2 of the row's 16 scale bytes
+                const int sb = ((kt & 7) << 1) + (ks >> 1);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const uint32_t raw = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(cB) +
+                                                                             ni * 32 * (BK / 2) + ks * 8 + frag_half * 4);
+                    const uint32_t w4[4] = {sc_cur[ni].x, sc_cur[ni].y, sc_cur[ni].z, sc_cur[ni].w};
+                    uint32_t word = w4[0];
+#pragma unroll
+                    for (int q = 1; q < 4; ++q) word = (sb >> 2) == q ? w4[q] : word;
+                    const float scale = __uint_as_float(((word >> ((sb & 3) << 3)) & 0xffu) << 23);  // 2^(byte - 127)
+                    const bf16x2 d0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 0);
+                    const bf16x2 d1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 1);
+                    const bf16x2 d2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 2);
+                    const bf16x2 d3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 3);
+                    const uint4 packed = make_uint4(*reinterpret_cast<const uint32_t *>(&d0),
+                                                    *reinterpret_cast<const uint32_t *>(&d1),
+                                                    *reinterpret_cast<const uint32_t *>(&d2),
+                                                    *reinterpret_cast<const uint32_t *>(&d3));
                     bfr[set][ni] = *reinterpret_cast<const bf16x8 *>(&packed);
                 }
             } else {
@@ -480,6 +514,23 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                     }
                     b_off[i] = ((grp - gn0) * group_bytes + (r & 15) * 64 + kc * 16) / 2;
                 }
+            } else if constexpr (B4) {
+                // one instruction = 1 KB = 32 rows of 32 bytes: lane L lands in row (L >> 1), 16-byte half
+                // (L & 1); in memory that 1 KB block is contiguous and the blocks of a 32-row group follow
+                // each other along K (the quantiser's layout)
+                const uint8_t *Bg4 = reinterpret_cast<const uint8_t *>(Bg0) + (int64_t)ti.expert * p.strideB;
+                const int group_bytes = (K / BK) * 1024;
+                const int last_group = p.N / 32 - 1;
+#pragma unroll
+                for (int i = 0; i < B_IT; ++i) {
+                    const int r = (wave * B_IT + i) * 32 + (lane >> 1);
+                    const int grp = min((ti.n0 + r) >> 5, last_group);
+                    if (i == 0) {
+                        gn0 = grp;
+                        b_base = reinterpret_cast<const uint16_t *>(Bg4 + (int64_t)grp * group_bytes);
+                    }
+                    b_off[i] = ((grp - gn0) * group_bytes + (r & 31) * 32 + (lane & 1) * 16) / 2;
+                }
             } else {
 #pragma unroll
                 for (int i = 0; i < B_IT; ++i) {
@@ -501,7 +552,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                                  (lds_void *)(sA + buf * BM * BK + (wave * A_IT + i) * 8 * BK), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < B_IT; ++i)
-                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * (B8 ? 512 : BK))),
+                __builtin_amdgcn_global_load_lds((const glb_void *)(b_base + (b_off[i] + kt * (BQ != 0 ? 512 : BK))),
                                                  (lds_void *)(sB + buf * BTILE + (wave * B_IT + i) * 8 * BK), 16, 0, 0);
         };
         // The loads run STAGES-1 K tiles ahead of the MFMAs along the block's whole sequence of
@@ -659,6 +710,28 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 }
             }
         };
+        // 4-bit weights: the scale bytes run one group of 8 K tiles ahead of the MFMAs, across tile borders
+        int s_seq = seq, s_grp = 0;
+        auto load_scales = [&](uint4(&dst)[B4 ? NI : 1]) {
+            if constexpr (B4) {
+                const TileInfo ts = tile_info(s_seq);
+                const int groups = (KT + 7) >> 3;  // 16-byte scale groups per weight row
+                const uint8_t *sb = p.b_blk_scale + (int64_t)ts.expert * p.stride_blk_scale;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int ng = min((ts.n0 + wn * WTN + ni * 32) >> 5, p.N / 32 - 1);
+                    dst[ni] = *reinterpret_cast<const uint4 *>(sb + ((int64_t)ng * groups + s_grp) * 512 + frag_row * 16);
+                }
+                if (++s_grp == groups) {  // on to the next tile of this block, if there is one
+                    s_grp = 0;
+                    if (seq_ok(s_seq + slots)) s_seq += slots;
+                }
+            }
+        };
+        if constexpr (B4) {
+            load_scales(sc_cur);
+            load_scales(sc_nxt);
+        }
 #pragma unroll
         for (int i = 0; i < STAGES - 1; ++i) issue_next();
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WAITN) : "memory");
@@ -667,8 +740,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         while (true) {
             zero_acc();
             for (int kt = 0; kt < KT; ++kt) {
+                if constexpr (B4) {
+                    if ((kt & 7) == 0 && (kt > 0 || seq != (int)(blockIdx.x >> 3))) {  // a new group of 8 K tiles
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) sc_cur[ni] = sc_nxt[ni];
+                        load_scales(sc_nxt);
+                    }
+                }
                 issue_next();  // into the stage the previous iteration computed from
-                compute(stage);
+                compute(stage, kt);
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WAITN) : "memory");
                 stage_barrier();
                 stage = (stage + 1 == STAGES) ? 0 : stage + 1;
@@ -729,7 +809,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             for (int kt = 0; kt < KT; ++kt) {
                 const int cur = kt & 1;
                 if (kt + 1 < KT) load_global(kt + 1);
-                compute(cur);
+                compute(cur, kt);
                 if (kt + 1 < KT) store_lds(cur ^ 1);
                 __syncthreads();
             }
@@ -742,15 +822,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
 }
 
 template <int BM, int BN, int WM, int WN, bool OUT_F32, bool RELU, bool GROUPED, bool KFULL, int MINB, int STAGES,
-          bool B8 = false>
+          int BQ = 0>
 static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *main_grid)
 {
     GemmParams p = p_in;
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (B8 ? BN / 2 : BN)) * BK * sizeof(uint16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES, B8>;
+    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (BQ == 8 ? BN / 2 : BQ == 4 ? BN / 4 : BN)) * BK * sizeof(uint16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES, BQ>;
     static int blocks_per_cu = 0;  // per instantiation
     if (blocks_per_cu == 0) {
         MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -791,12 +871,12 @@ static int launch_one(const GemmParams &p, int num_cus, hipStream_t s, int *main
                : launch_k<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, false, MINB, 2>(p, num_cus, s, main_grid);
 }
 
-// grouped GEMM with 8-bit weights (K a multiple of the K tile: checked by the caller)
-template <int BM, int BN, int WM, int WN, int MINB, int STAGES>
+// grouped GEMM with 8-bit (BQ = 8) or 4-bit (BQ = 4) weights (K a multiple of the K tile: checked by the caller)
+template <int BM, int BN, int WM, int WN, int MINB, int STAGES, int BQ = 8>
 static int launch_grouped_w8(const GemmParams &p, bool relu, int num_cus, hipStream_t s)
 {
-    return relu ? launch_k<BM, BN, WM, WN, false, true, true, true, MINB, STAGES, true>(p, num_cus, s, nullptr)
-                : launch_k<BM, BN, WM, WN, false, false, true, true, MINB, STAGES, true>(p, num_cus, s, nullptr);
+    return relu ? launch_k<BM, BN, WM, WN, false, true, true, true, MINB, STAGES, BQ>(p, num_cus, s, nullptr)
+                : launch_k<BM, BN, WM, WN, false, false, true, true, MINB, STAGES, BQ>(p, num_cus, s, nullptr);
 }
 
 // Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves, pipeline)
@@ -847,12 +927,26 @@ int gemm_bf16_variant_w8(int64_t n_rows, int E)
     return avg >= 48 ? 22 : 23;
 }
 
+// 4-bit weights: 42 = 32x128, 43 = 32x256, 44 = 64x128 (four LDS stages each)
+int gemm_bf16_variant_w4(int64_t n_rows, int E)
+{
+    static int forced = -1;
+    if (forced < 0) {
+        const char *e = getenv("MOE355_W4_VARIANT");  // tuning override, 0 / unset = automatic
+        forced = e ? atoi(e) : 0;
+        if (forced < 42 || forced > 44) forced = 0;
+    }
+    if (forced) return forced;
+    const int64_t avg = E > 0 ? n_rows / E : n_rows;
+    return avg >= 48 ? 44 : 42;
+}
+
 int gemm_bf16_variant_block_m(int v)
 {
     switch (v) {
     case 1: case 10: return 128;
-    case 2: case 22: return 64;
-    case 3: case 23: return 32;
+    case 2: case 22: case 44: return 64;
+    case 3: case 23: case 42: case 43: return 32;
     default: return 256;
     }
 }
@@ -923,6 +1017,9 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
     case 1: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
     case 22: return launch_grouped_w8<64, 128, 1, 4, 2, 3>(p, relu, num_cus, s);
     case 23: return launch_grouped_w8<32, 128, 1, 4, 2, 4>(p, relu, num_cus, s);
+    case 42: return launch_grouped_w8<32, 128, 1, 4, 2, 4, 4>(p, relu, num_cus, s);
+    case 43: return launch_grouped_w8<32, 256, 1, 4, 2, 4, 4>(p, relu, num_cus, s);
+    case 44: return launch_grouped_w8<64, 128, 1, 4, 2, 4, 4>(p, relu, num_cus, s);
     case 2: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
     case 3: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
     default:

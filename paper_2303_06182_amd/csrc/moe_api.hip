@@ -65,6 +65,7 @@ int launch_gemm_f32(const GemmParams &p, bool grouped, bool relu, hipStream_t s)
 int gemm_f32_block_m();
 bool gemm_bf16_variant_gathers(int variant, int K);
 int gemm_bf16_variant_w8(int64_t n_rows, int E);
+int gemm_bf16_variant_w4(int64_t n_rows, int E);
 
 int gemm_variant(int dtype, int64_t n_rows, int E, int N, int num_cus)
 {
@@ -235,6 +236,15 @@ static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const fl
     return launch_topk(logits, T, c.E, c.k, c.renormalize, idx, w, s);
 }
 
+// scale bytes of one expert's [rows, cols] matrix in the 4-bit layout: 16 per row and 512 columns
+static int64_t mxfp4_scale_bytes(int64_t rows, int64_t cols) { return (rows / 32) * ((cols + 511) / 512) * 512; }
+
+// tile shape of the grouped GEMM for quantised weights
+static int quant_variant(int wbits, int64_t n_rows, int E)
+{
+    return wbits == 4 ? gemm_bf16_variant_w4(n_rows, E) : gemm_bf16_variant_w8(n_rows, E);
+}
+
 // Options of the grouped FFN beyond the plain call.
 struct FfnExtra {
     // xp is the token array and row r of the experts' input is its row a_rows[r] (dispatch fused
@@ -249,8 +259,10 @@ struct FfnExtra {
     // the routing step has already written the tile map for M tiles of this height (0 = it has not)
     int tile_map_ready_bm = 0;
     // 8-bit weights: w1 / w2 are e4m3 bytes, one fp32 scale per expert and matrix
-    const float *w1_scale = nullptr;
+    const float *w1_scale = nullptr;     // 8-bit weights: per-expert scales
     const float *w2_scale = nullptr;
+    const uint8_t *w1_blk = nullptr;     // 4-bit weights: block scale bytes
+    const uint8_t *w2_blk = nullptr;
 };
 
 // Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows, F] and the tile arrays are scratch.
@@ -262,9 +274,9 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
     if (n_rows == 0) return MOE_OK;
     // each GEMM picks its own tile shape (N differs: F for the first, D for the second); the tile
     // map is rebuilt between them only when the M tile height differs
-    const bool w8 = ex.w1_scale != nullptr;
-    const int v1 = w8 ? gemm_bf16_variant_w8(n_rows, c.E) : gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus);
-    const int v2 = w8 ? v1 : gemm_variant(c.dtype, n_rows, c.E, c.D, h->num_cus);
+    const int wbits = ex.w1_blk ? 4 : ex.w1_scale ? 8 : 0;
+    const int v1 = wbits ? quant_variant(wbits, n_rows, c.E) : gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus);
+    const int v2 = wbits ? v1 : gemm_variant(c.dtype, n_rows, c.E, c.D, h->num_cus);
     const int bm1 = gemm_variant_block_m(c.dtype, v1), bm2 = gemm_variant_block_m(c.dtype, v2);
     int max_tiles = (int)(n_rows / bm1) + c.E + 1;
     int rc = MOE_OK;
@@ -289,7 +301,9 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
     p.b_slot = ex.b_slot;
     p.b_scale = ex.w1_scale;
     p.ldb = c.D;
-    p.strideB = ex.b_slot ? ex.slot_stride : (int64_t)c.F * c.D;
+    p.strideB = ex.b_slot ? ex.slot_stride : (int64_t)c.F * c.D / (wbits == 4 ? 2 : 1);  // elements; bytes for 8 and 4 bits
+    p.b_blk_scale = ex.w1_blk;
+    p.stride_blk_scale = mxfp4_scale_bytes(c.F, c.D);
     p.bias = b1;
     p.strideBias = c.F;
     p.C = hbuf;
@@ -311,7 +325,9 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
     p.B = w2;
     p.b_scale = ex.w2_scale;
     p.ldb = c.F;
-    p.strideB = ex.b_slot ? ex.slot_stride : (int64_t)c.D * c.F;
+    p.strideB = ex.b_slot ? ex.slot_stride : (int64_t)c.D * c.F / (wbits == 4 ? 2 : 1);
+    p.b_blk_scale = ex.w2_blk;
+    p.stride_blk_scale = mxfp4_scale_bytes(c.D, c.F);
     p.bias = b2;
     p.strideBias = c.D;
     p.C = yp;
@@ -322,7 +338,7 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
 }
 
 // Can the first expert GEMM gather its rows from the token array (T tokens) itself?
-static bool fused_dispatch_ok(const moe_handle_t *h, int64_t T, bool w8 = false)
+static bool fused_dispatch_ok(const moe_handle_t *h, int64_t T, int wbits = 0)
 {
     static int off = -1;
     if (off < 0) {
@@ -331,16 +347,16 @@ static bool fused_dispatch_ok(const moe_handle_t *h, int64_t T, bool w8 = false)
     }
     const moe_config_t &c = h->cfg;
     if (off || c.dtype != MOE_DTYPE_BF16 || T * c.D >= ((int64_t)1 << 31)) return false;
-    const int v = w8 ? gemm_bf16_variant_w8(T * c.k, c.E) : gemm_variant(c.dtype, T * c.k, c.E, c.F, h->num_cus);
+    const int v = wbits ? quant_variant(wbits, T * c.k, c.E) : gemm_variant(c.dtype, T * c.k, c.E, c.F, h->num_cus);
     return gemm_bf16_variant_gathers(v, c.D);
 }
 
-// 8-bit weights need bf16 activations and K dimensions that are whole K tiles
+// 8- and 4-bit weights need bf16 activations and K dimensions that are whole K tiles
 static int check_w8(const moe_handle_t *h)
 {
     const moe_config_t &c = h->cfg;
     if (c.dtype != MOE_DTYPE_BF16 || c.D % 64 != 0 || c.F % 64 != 0) {
-        set_error("8-bit expert weights need dtype bf16 and D, F multiples of 64 (D = %d, F = %d)", c.D, c.F);
+        set_error("8- and 4-bit expert weights need dtype bf16 and D, F multiples of 64 (D = %d, F = %d)", c.D, c.F);
         return MOE_ERR_UNSUPPORTED;
     }
     return MOE_OK;
@@ -646,12 +662,14 @@ static int buffered_expert_ffn(moe_handle_t *h, moe_expert_cache_t *cache, const
                                int32_t n_rows, void *yp, void *workspace, hipStream_t s);
 
 // cache == NULL: experts from w1 / w2 in device memory; else buffered (w1, w2 unused)
-// w1_scale != NULL: w1 / w2 are e4m3 bytes with these per-expert scales
+// w1_scale != NULL: w1 / w2 are e4m3 bytes with these per-expert scales; w1_blk != NULL: e2m1 nibbles
+// with these block scale bytes
 static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const void *x, const void *wg,
                               const float *gate_bias, const void *w1, const void *w2, const void *b1, const void *b2,
                               int32_t T, void *y, const moe_routing_t *routing_out, void *workspace,
                               int64_t workspace_bytes, void *stream, const float *w1_scale = nullptr,
-                              const float *w2_scale = nullptr)
+                              const float *w2_scale = nullptr, const uint8_t *w1_blk = nullptr,
+                              const uint8_t *w2_blk = nullptr)
 {
     g_err[0] = 0;
     ProfBind bind(h);
@@ -692,16 +710,16 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
     // the routing step's scan kernel also writes the first expert GEMM's tile map (not when the
     // experts are buffered: their tile maps are per stage)
     const int64_t n_rows = (int64_t)T * c.k;
-    const bool w8 = w1_scale != nullptr;
+    const int wbits = w1_blk ? 4 : w1_scale ? 8 : 0;
     const int bm1 = cache ? 0
-                          : gemm_variant_block_m(c.dtype, w8 ? gemm_bf16_variant_w8(n_rows, c.E)
-                                                             : gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus));
+                          : gemm_variant_block_m(c.dtype, wbits ? quant_variant(wbits, n_rows, c.E)
+                                                                : gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus));
     rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, at<int32_t>(workspace, L.block_hist), s, bm1,
                       at<int32_t>(workspace, L.tile_expert), at<int32_t>(workspace, L.tile_row),
                       at<int32_t>(workspace, L.num_tiles), bm1 > 0 ? (int)(n_rows / bm1) + c.E + 1 : 0);
     if (rc != MOE_OK) return rc;
     // dispatch: a scatter of its own, or folded into the first GEMM's row addressing (then Xp is never written)
-    const bool fused = fused_dispatch_ok(h, T, w8);
+    const bool fused = fused_dispatch_ok(h, T, wbits);
     if (!fused) {
         rc = launch_dispatch(c.dtype, x, dst_row, T, c.D, c.k, xp, s);
         if (rc != MOE_OK) return rc;
@@ -715,6 +733,8 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
         ex.tile_map_ready_bm = bm1;
         ex.w1_scale = w1_scale;
         ex.w2_scale = w2_scale;
+        ex.w1_blk = w1_blk;
+        ex.w2_blk = w2_blk;
         rc = do_expert_ffn(h, fused ? x : xp, ex, offsets, w1, w2, b1, b2, T * c.k, yp, workspace, s);
     }
     if (rc != MOE_OK) return rc;
@@ -793,6 +813,82 @@ int moe_layer_forward_w8(moe_handle_t *h, const void *x, const void *wg, const f
     static const float one = 1.f;  // T = 0: nothing reads the scales, the pointer only selects the path
     return layer_forward_impl(h, nullptr, x, wg, gate_bias, w1_q, w2_q, b1, b2, T, y, routing_out, workspace,
                               workspace_bytes, stream, w1_scale ? w1_scale : &one, w2_scale ? w2_scale : &one);
+}
+
+// ---- 4-bit expert weights with block scales -------------------------------------------------------
+int64_t moe_mxfp4_scale_bytes(int32_t rows, int32_t cols)
+{
+    g_err[0] = 0;
+    if (rows < 32 || rows % 32 != 0 || cols < 64 || cols % 64 != 0) {
+        set_error("mxfp4: rows = %d not a positive multiple of 32 or cols = %d not a positive multiple of 64", rows, cols);
+        return MOE_ERR_INVALID_ARG;
+    }
+    return mxfp4_scale_bytes(rows, cols);
+}
+
+int moe_quantize_mxfp4(moe_handle_t *h, const void *w, int32_t E, int32_t rows, int32_t cols, void *q_out,
+                       void *scale_out, void *stream)
+{
+    g_err[0] = 0;
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (E < 1 || E > 65535 || rows < 32 || rows % 32 != 0 || cols < 64 || cols % 64 != 0) {
+        set_error("quantize: E = %d outside [1, 65535], rows = %d not a positive multiple of 32 or cols = %d not a "
+                  "positive multiple of 64", E, rows, cols);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (bad_ptr(w, "w") || bad_ptr(q_out, "q_out") || bad_ptr(scale_out, "scale_out")) return MOE_ERR_INVALID_ARG;
+    return launch_quantize_mxfp4(h->cfg.dtype, w, E, rows, cols, static_cast<uint8_t *>(q_out),
+                                 static_cast<uint8_t *>(scale_out), (hipStream_t)stream);
+}
+
+int moe_expert_ffn_w4(moe_handle_t *h, const void *xp, const int32_t *offsets, const void *w1_q, const void *w2_q,
+                      const void *w1_scale, const void *w2_scale, const void *b1, const void *b2, int32_t n_rows,
+                      void *yp, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    g_err[0] = 0;
+    ProfBind bind(h);
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    int rc = check_w8(h);
+    if (rc != MOE_OK) return rc;
+    if (n_rows < 0 || (int64_t)n_rows > (int64_t)h->cfg.T_max * h->cfg.k) {
+        set_error("n_rows = %d outside [0, k*T_max = %lld]", n_rows, (long long)h->cfg.T_max * h->cfg.k);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (n_rows == 0) return MOE_OK;
+    if (bad_ptr(xp, "xp") || bad_ptr(offsets, "offsets") || bad_ptr(w1_q, "w1_q") || bad_ptr(w2_q, "w2_q") ||
+        bad_ptr(w1_scale, "w1_scale") || bad_ptr(w2_scale, "w2_scale") || bad_ptr(b1, "b1", true) ||
+        bad_ptr(b2, "b2", true) || bad_ptr(yp, "yp"))
+        return MOE_ERR_INVALID_ARG;
+    rc = check_ws(h, workspace, workspace_bytes);
+    if (rc != MOE_OK) return rc;
+    FfnExtra ex;
+    ex.w1_blk = static_cast<const uint8_t *>(w1_scale);
+    ex.w2_blk = static_cast<const uint8_t *>(w2_scale);
+    return do_expert_ffn(h, xp, ex, offsets, w1_q, w2_q, b1, b2, n_rows, yp, workspace, (hipStream_t)stream);
+}
+
+int moe_layer_forward_w4(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1_q,
+                         const void *w2_q, const void *w1_scale, const void *w2_scale, const void *b1,
+                         const void *b2, int32_t T, void *y, const moe_routing_t *routing_out, void *workspace,
+                         int64_t workspace_bytes, void *stream)
+{
+    g_err[0] = 0;
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    int rc = check_w8(h);
+    if (rc != MOE_OK) return rc;
+    if (bad_ptr(w1_scale, "w1_scale") || bad_ptr(w2_scale, "w2_scale")) return MOE_ERR_INVALID_ARG;
+    return layer_forward_impl(h, nullptr, x, wg, gate_bias, w1_q, w2_q, b1, b2, T, y, routing_out, workspace,
+                              workspace_bytes, stream, nullptr, nullptr, static_cast<const uint8_t *>(w1_scale),
+                              static_cast<const uint8_t *>(w2_scale));
 }
 
 // ---- expert buffering ------------------------------------------------------------------------

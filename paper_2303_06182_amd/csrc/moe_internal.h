@@ -99,6 +99,8 @@ struct GemmParams {
     int64_t strideB;     // elements between experts (between slots with b_slot)
     const int32_t *b_slot;  // grouped: expert e's weights are slot b_slot[e] of B (NULL = e)
     const float *b_scale;   // 8-bit weight variants: fp32 scale per expert (NULL = 1)
+    const uint8_t *b_blk_scale;  // 4-bit weight variants: e8m0 scale bytes, per expert [N/32][ceil(K/512)][32][16]
+    int64_t stride_blk_scale;    // bytes between two experts' scale arrays
     const void *bias;    // elem [N] / [E,N], or NULL
     int64_t strideBias;
     const float *bias_f32;  // fp32 [N] or NULL (gate offsets)
@@ -135,6 +137,8 @@ int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool 
 // per_expert a multiple of 4.
 int launch_quantize_e4m3(int dtype, const void *w, int E, int rows, int cols, uint8_t *q, float *scale,
                          hipStream_t s);
+int launch_quantize_mxfp4(int dtype, const void *w, int E, int rows, int cols, uint8_t *q, uint8_t *scales,
+                          hipStream_t s);
 
 // Tile map for the grouped GEMM from the device-side offsets (one block).
 // stage_of != NULL: only the experts e with stage_of[e] == stage get tiles.

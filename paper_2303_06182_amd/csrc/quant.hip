@@ -93,6 +93,87 @@ __global__ void finish_scale_kernel(uint32_t *__restrict__ bits_then_scale, int 
     if (e < E) bits_then_scale[e] = __float_as_uint(scale_of(__uint_as_float(bits_then_scale[e])));
 }
 
+// ---- 4-bit weights with block scales (the OCP microscaling layout: e2m1 elements, one e8m0 scale per
+// 32 elements along the row) ------------------------------------------------------------------------
+// Element values: code & 7 -> 0, 0.5, 1, 1.5, 2, 3, 4, 6; bit 3 is the sign.  The block scale is the
+// smallest power of two s with max|block| <= 6 s (so nothing saturates), stored as the byte s = 2^(b - 127),
+// b >= 1; an all-zero block gets b = 127.  Rounding to nearest, ties to the even code.
+// Byte layouts, both made for the grouped GEMM: data, 32 rows x 64 columns per contiguous 1 KB (row r of
+// the block at byte 32 r, two elements per byte, the lower column in the low nibble), the blocks of a
+// 32-row group one after the other along the columns; scales, 32 rows x 16 bytes per contiguous 512 B (the
+// 16 scales of 512 columns), again group by group along the columns, the last 512-column group padded.
+__device__ __forceinline__ uint32_t e2m1_code(float v)
+{
+    const float a = fabsf(v);
+    uint32_t c;
+    if (a <= 0.25f) c = 0;
+    else if (a < 0.75f) c = 1;
+    else if (a <= 1.25f) c = 2;
+    else if (a < 1.75f) c = 3;
+    else if (a <= 2.5f) c = 4;
+    else if (a < 3.5f) c = 5;
+    else if (a <= 5.0f) c = 6;
+    else c = 7;
+    return c | (__float_as_uint(v) >> 31 << 3);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kQThreads) void quantize_mxfp4_kernel(const void *__restrict__ w, int rows, int cols,
+                                                                   uint8_t *__restrict__ q, uint8_t *__restrict__ scales)
+{
+    const int e = blockIdx.y;
+    const int64_t per_expert = (int64_t)rows * cols;
+    const int kblocks = cols >> 6, kgroups = (cols + 511) >> 9;
+    const int64_t q_expert = per_expert / 2, s_expert = (int64_t)(rows >> 5) * kgroups * 512;
+    // eight elements of one row per thread and step; four neighbouring lanes hold one 32-element block.
+    // per_expert is a multiple of 2048 (32 rows x 64 columns), so whole waves stay inside the range.
+    for (int64_t i = ((int64_t)blockIdx.x * kQThreads + threadIdx.x) * 8; i < per_expert;
+         i += (int64_t)gridDim.x * kQThreads * 8) {
+        float v[8];
+        load4<BF16>(w, (int64_t)e * per_expert + i, *reinterpret_cast<float(*)[4]>(&v[0]));
+        load4<BF16>(w, (int64_t)e * per_expert + i + 4, *reinterpret_cast<float(*)[4]>(&v[4]));
+        float m = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(v[j]));
+        m = fmaxf(m, __shfl_xor(m, 1, 64));
+        m = fmaxf(m, __shfl_xor(m, 2, 64));
+        // smallest n with m <= 6 * 2^n: m = mant * 2^ex, mant in [0.5, 1), 6 = 0.75 * 2^3
+        int n = 0;
+        if (m > 0.f) {
+            int ex;
+            const float mant = frexpf(m, &ex);
+            n = mant <= 0.75f ? ex - 3 : ex - 2;
+            n = n < -126 ? -126 : n;
+        }
+        const float inv = ldexpf(1.f, -n);  // exact
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) word |= e2m1_code(v[j] * inv) << (4 * j);
+        const int64_t r = i / cols;
+        const int k = (int)(i - r * cols);
+        *reinterpret_cast<uint32_t *>(q + e * q_expert + ((r >> 5) * kblocks + (k >> 6)) * 1024 + (r & 31) * 32 +
+                                      ((k & 63) >> 1)) = word;
+        if ((k & 31) == 0)
+            scales[e * s_expert + ((r >> 5) * kgroups + (k >> 9)) * 512 + (r & 31) * 16 + ((k & 511) >> 5)] =
+                (uint8_t)(n + 127);
+    }
+}
+
+int launch_quantize_mxfp4(int dtype, const void *w, int E, int rows, int cols, uint8_t *q, uint8_t *scales, hipStream_t s)
+{
+    const int64_t per_expert = (int64_t)rows * cols;
+    int64_t bx = (per_expert / 8 + kQThreads * 4 - 1) / (kQThreads * 4);
+    if (bx > 512) bx = 512;
+    if (bx < 1) bx = 1;
+    const dim3 grid((unsigned)bx, (unsigned)E);
+    if (dtype == MOE_DTYPE_BF16)
+        hipLaunchKernelGGL(quantize_mxfp4_kernel<true>, grid, dim3(kQThreads), 0, s, w, rows, cols, q, scales);
+    else
+        hipLaunchKernelGGL(quantize_mxfp4_kernel<false>, grid, dim3(kQThreads), 0, s, w, rows, cols, q, scales);
+    MOE_LAUNCH_CHECK("quantize_mxfp4");
+    return MOE_OK;
+}
+
 int launch_quantize_e4m3(int dtype, const void *w, int E, int rows, int cols, uint8_t *q, float *scale, hipStream_t s)
 {
     const int64_t per_expert = (int64_t)rows * cols;
