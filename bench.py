@@ -260,10 +260,10 @@ def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho):
     return out
 
 
-def run_w8(name, steps=20, warmup=4, profile_steps=5):
-    """The same workload with the expert weights stored as e4m3 bytes (moe_layer_forward_w8) beside
-    the bf16-weight layer: whole-layer time and the two expert GEMMs against the HBM roof, with the
-    weight bytes halved in the algorithmic count."""
+def run_weight_formats(name, steps=20, warmup=4, profile_steps=5):
+    """The same workload with the expert weights stored as bf16, as e4m3 bytes (moe_layer_forward_w8)
+    and as e2m1 nibbles with block scales (moe_layer_forward_w4): whole-layer time and the two expert
+    GEMMs against the HBM roof, the weight bytes counted at their stored size."""
     import numpy as np
     import torch
     from paper_2303_06182_amd import binding, workloads as wl
@@ -275,6 +275,8 @@ def run_w8(name, steps=20, warmup=4, profile_steps=5):
     routing = layer.empty_routing(w.T)
     q1, s1 = layer.moe_quantize_e4m3(inp["w1"])
     q2, s2 = layer.moe_quantize_e4m3(inp["w2"])
+    p1, t1 = layer.moe_quantize_mxfp4(inp["w1"])
+    p2, t2 = layer.moe_quantize_mxfp4(inp["w2"])
     torch.cuda.synchronize()
 
     def step16():
@@ -283,8 +285,12 @@ def run_w8(name, steps=20, warmup=4, profile_steps=5):
     def step8():
         layer.moe_layer_forward_w8(inp["x"], inp["wg"], q1, q2, s1, s2, inp["gate_bias"], y=y, routing_out=routing)
 
+    def step4():
+        layer.moe_layer_forward_w4(inp["x"], inp["wg"], p1, p2, t1, t2, inp["gate_bias"], y=y, routing_out=routing)
+
     out = {}
-    for label, step, wbytes in (("bf16_weights", step16, 2), ("e4m3_weights", step8, 1)):
+    # bytes per weight: 4-bit elements plus one scale byte per 32
+    for label, step, wbytes in (("bf16", step16, 2.0), ("e4m3", step8, 1.0), ("mxfp4", step4, 0.5 + 1.0 / 32)):
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
@@ -304,13 +310,14 @@ def run_w8(name, steps=20, warmup=4, profile_steps=5):
         gemms = {}
         for kname in ("expert_gemm1", "expert_gemm2"):
             kms = float(np.mean(acc[kname]))
-            nbytes = e_active * w.F * w.D * wbytes + N * (w.D + w.F) * 2
+            nbytes = int(e_active * w.F * w.D * wbytes) + N * (w.D + w.F) * 2
             gemms[kname] = dict(avg_ms=kms, algorithmic_bytes=nbytes, achieved=nbytes / (kms * 1e-3) / 1e9,
                                 unit="GB/s", frac=nbytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS)
         out[label] = dict(ms_per_step=ms, tokens_per_s=w.T / (ms * 1e-3), kernels=gemms)
-    out["speedup"] = out["bf16_weights"]["ms_per_step"] / out["e4m3_weights"]["ms_per_step"]
+    out["speedup_e4m3"] = out["bf16"]["ms_per_step"] / out["e4m3"]["ms_per_step"]
+    out["speedup_mxfp4"] = out["bf16"]["ms_per_step"] / out["mxfp4"]["ms_per_step"]
     out["workload"] = name
-    del layer, inp, y, routing, q1, q2
+    del layer, inp, y, routing, q1, q2, p1, p2
     torch.cuda.empty_cache()
     return out
 
@@ -351,7 +358,7 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the CPU oracle's FFN sample (0 = skip)")
     ap.add_argument("--no-static", action="store_true", help="skip the static-capacity baseline runs")
     ap.add_argument("--no-buffering", action="store_true", help="skip the expert-buffering runs")
-    ap.add_argument("--no-w8", action="store_true", help="skip the 8-bit expert-weight run (mt_decoder)")
+    ap.add_argument("--no-w8", action="store_true", help="skip the run with 8- and 4-bit expert weights (mt_decoder)")
     ap.add_argument("--buffering-steps", type=int, default=16, help="decode steps of the expert-buffering runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write elementwise kernel three times (untimed): gives counter runs "
@@ -396,7 +403,7 @@ def main():
     buffering = None
     if not args.no_buffering:
         buffering = run_buffering("mt_decoder", [16, 48, 96], args.buffering_steps)
-    w8 = None if args.no_w8 else run_w8("mt_decoder")
+    w8 = None if args.no_w8 else run_weight_formats("mt_decoder")
     cpu = cpu_baseline(args.config, main_res["host"], args.cpu_tokens) if args.cpu_tokens > 0 else None
 
     dom = dict(main_res["dominant"])
@@ -424,7 +431,7 @@ def main():
         "also": also,
         "static_baseline": static,
         "expert_buffering": buffering,
-        "weights_e4m3": w8,
+        "weight_formats": w8,
         "paper_context": "paper reports only relative whole-model speedups of dynamic over static gating on "
                          "8xV100 nodes (LM 6.21-11.23x, MT encoder 5.75-10.98x, MT decoder 2.58-5.71x); "
                          "no absolute number exists for this metric",
