@@ -82,6 +82,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 
 struct TileInfo {
     int row0, row_end, expert, n0;
+    int kt0, split;  // plain mode with split K: first K tile and index of this block's K range
 };
 
 // BQ: storage of the B operand (the weights).  0: bf16.  8: 8-bit floats (OCP e4m3, one byte per
@@ -123,7 +124,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     const int wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int K = p.K;
-    const int KT = (K + BK - 1) / BK;
+    // Split K (plain mode, skinny problems: the gate GEMM of a decoder step has a tile or two and a long K
+    // loop): the K tiles are cut into k_split equal ranges, each a tile of its own whose fp32 result goes to
+    // its own slice (range 0 to C, range i > 0 to c_parts + (i - 1) * split_stride); whoever reads C adds the
+    // slices in order.
+    const int S = (!GROUPED && p.k_split > 1) ? p.k_split : 1;
+    const int KT = (K + BK - 1) / BK / S;  // the launcher made sure that S divides the K tile count
 
     // ---- the block's sequence of tiles -----------------------------------------------------------
     // Tail splitting (grouped GEMM over 256x256 tiles): a persistent launch of G blocks runs
@@ -139,7 +145,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     const bool tail_sub = GROUPED && p.tail_mode == 2;
     const int n_tiles = (p.N + (tail_sub ? PT : BN) - 1) / (tail_sub ? PT : BN);  // of the tile list's geometry
     const int m_tiles = GROUPED ? p.num_tiles[0] : (p.M + BM - 1) / BM;
-    int live = m_tiles * n_tiles;              // logical tiles
+    int live = m_tiles * n_tiles * S;          // logical tiles
     int cut = 0;                               // first parent tile of the tail
     if (GROUPED && (p.tail_mode == 1 || p.tail_mode == 2)) {
         const int left = live % p.main_slots;
@@ -155,7 +161,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     // inside a group the M index runs fastest
     auto tile_info = [&](int sq) {
         int lid = xcd * chunk + sq;
-        int sub = 0;
+        int sub = 0, split = 0;
+        if (S > 1) {
+            split = lid % S;
+            lid /= S;
+        }
         if (tail_sub) {
             sub = lid % SUB;
             lid = cut + lid / SUB;
@@ -177,6 +187,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             t.row_end = p.M;
         }
         t.n0 = nt * BN;
+        t.kt0 = split * KT;
+        t.split = split;
         if (tail_sub) {  // sub-tile (sub / SUB_N, sub % SUB_N) of the 256x256 parent
             t.row0 += (sub / SUB_N) * BM;
             t.n0 = nt * PT + (sub % SUB_N) * BN;
@@ -307,7 +319,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         // issued between stores would have to wait for every store before it (memory operations
         // of a wave complete in order), once per group of four columns.
         float bias32[NI][4][4];
-        if (p.bias_f32) {
+        const bool add_bias32 = p.bias_f32 && t.split == 0;
+        if (add_bias32) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -352,7 +365,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                 if (col + i < p.N) v[i] += from_bf16(bias[col + i]);
                         }
                     }
-                    if (p.bias_f32) {
+                    if (add_bias32) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) v[i] += bias32[ni][g][i];
                     }
@@ -361,7 +374,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                         for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.f ? v[i] : 0.f;
                     }
                     if (OUT_F32) {
-                        float *c = static_cast<float *>(p.C) + (int64_t)row * p.ldc + col;
+                        float *c = (t.split == 0 ? static_cast<float *>(p.C) : p.c_parts + (int64_t)(t.split - 1) * p.split_stride) +
+                                   (int64_t)row * p.ldc + col;
                         if (vec_ok) {
                             *reinterpret_cast<float4 *>(c) = make_float4(v[0], v[1], v[2], v[3]);
                         } else {
@@ -489,7 +503,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 if (GROUPED && p.a_rows) gr = p.a_rows[gr];
                 if (i == 0) {
                     gr0 = gr;
-                    a_base = Ag + (int64_t)gr * p.lda;
+                    a_base = Ag + (int64_t)gr * p.lda + ti.kt0 * BK;
                 }
                 a_off[i] = (gr - gr0) * (int)p.lda + kc * 8;
             }
@@ -539,7 +553,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                     const int gn = min(ti.n0 + r, p.N - 1);
                     if (i == 0) {
                         gn0 = gn;
-                        b_base = Bg + (int64_t)gn * p.ldb;
+                        b_base = Bg + (int64_t)gn * p.ldb + ti.kt0 * BK;
                     }
                     b_off[i] = (gn - gn0) * p.ldb + kc * 8;
                 }
@@ -842,6 +856,13 @@ static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *mai
     // persistent grid: every resident slot of the chip, but never more blocks than upper-bound tiles
     int64_t grid = (int64_t)num_cus * blocks_per_cu;
     int64_t tiles = (int64_t)m_tiles * n_tiles;
+    if (!GROUPED && p.k_split > 1) {
+        if (!KFULL || (p.K / BK) % p.k_split != 0) {
+            set_error("split K: %d does not divide the %d K tiles", p.k_split, p.K / BK);
+            return MOE_ERR_INVALID_ARG;
+        }
+        tiles *= p.k_split;
+    }
     if (p.tail_mode == 2) {
         // max_m_tiles counts 256-row parents; at most (main_slots * 5 - 1) / 9 of the parent tiles are left over
         p.main_slots = *main_grid;
@@ -941,6 +962,21 @@ int gemm_bf16_variant_w4(int64_t n_rows, int E)
     if (forced) return forced;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
     return avg >= 96 ? 48 : 43;
+}
+
+// K ranges for the fp32-output plain GEMM (the gate): 1 unless the 32-row tiles would leave most of the
+// chip idle; then the largest power of two <= 16 that divides the K tile count, keeps two K tiles per
+// range and does not make more tiles than CUs.
+int gemm_bf16_gate_split(int M, int N, int K, int num_cus)
+{
+    if (K % BK != 0) return 1;
+    const int bn = N <= 32 ? 32 : (N <= 64 ? 64 : 128);
+    const int64_t tiles = (int64_t)ceil_div(M, 32) * ceil_div(N, bn);
+    if ((int64_t)ceil_div(M, 128) * ceil_div(N, 128) >= 2 * (int64_t)num_cus) return 1;  // the 128-row shape runs
+    const int kt = K / BK;
+    int s = 1;
+    while (s * 2 <= 16 && kt % (s * 2) == 0 && kt / (s * 2) >= 2 && tiles * s * 2 <= num_cus) s *= 2;
+    return s;
 }
 
 int gemm_bf16_variant_block_m(int v)

@@ -66,6 +66,7 @@ int gemm_f32_block_m();
 bool gemm_bf16_variant_gathers(int variant, int K);
 int gemm_bf16_variant_w8(int64_t n_rows, int E);
 int gemm_bf16_variant_w4(int64_t n_rows, int E);
+int gemm_bf16_gate_split(int M, int N, int K, int num_cus);
 
 int gemm_variant(int dtype, int64_t n_rows, int E, int N, int num_cus)
 {
@@ -87,10 +88,12 @@ int launch_gemm(int dtype, const GemmParams &p, bool grouped, int variant, bool 
 
 // ---- workspace ---------------------------------------------------------------------------------
 static constexpr int kMinBlockM = 32;  // smallest M tile any grouped GEMM uses: sizes the tile map
+// split K of the gate GEMM: at most this many K ranges, only for this many tokens or fewer (sizes the slices)
+static constexpr int kGateSplitMax = 16, kGateSplitTokens = 256;
 
 struct WsLayout {
     int64_t logits, topk_idx, topk_w, counts, offsets, dst_row, src_tok, block_hist;
-    int64_t tile_expert, tile_row, num_tiles, xp, h, yp, total;
+    int64_t tile_expert, tile_row, num_tiles, gate_parts, xp, h, yp, total;
 };
 
 static int elem_size(int dtype) { return dtype == MOE_DTYPE_BF16 ? 2 : 4; }
@@ -117,6 +120,7 @@ static WsLayout ws_layout(const moe_config_t &c)
     L.tile_expert = take(max_tiles * 4);
     L.tile_row = take(max_tiles * 4);
     L.num_tiles = take(4);
+    L.gate_parts = take((int64_t)(kGateSplitMax - 1) * (T < kGateSplitTokens ? T : kGateSplitTokens) * E * 4);
     L.xp = take(N * c.D * es);
     L.h = take(N * c.F * es);
     L.yp = take(N * c.D * es);
@@ -214,11 +218,18 @@ static int validate_config(const moe_config_t *c)
 }
 
 // ---- the five steps ------------------------------------------------------------------------------
+// parts: room for (kGateSplitMax - 1) * min(T_max, kGateSplitTokens) * E floats, or NULL.  A decoder step's
+// gate GEMM (a tile or two, a long K loop) is cut along K into slices that the top-k kernel adds up.
 static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, int T,
-                        float *logits, int32_t *idx, float *w, hipStream_t s)
+                        float *logits, int32_t *idx, float *w, hipStream_t s, float *parts = nullptr)
 {
     const moe_config_t &c = h->cfg;
     if (T == 0) return MOE_OK;
+    int split = 1;
+    if (parts && c.dtype == MOE_DTYPE_BF16 && T <= kGateSplitTokens) {
+        split = gemm_bf16_gate_split(T, c.E, c.D, h->num_cus);
+        if (split > kGateSplitMax) split = kGateSplitMax;
+    }
     GemmParams p;
     memset(&p, 0, sizeof(p));
     p.A = x;
@@ -231,9 +242,14 @@ static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const fl
     p.M = T;
     p.N = c.E;
     p.K = c.D;
+    if (split > 1) {
+        p.k_split = split;
+        p.c_parts = parts;
+        p.split_stride = (int64_t)T * c.E;
+    }
     int rc = launch_gemm(c.dtype, p, false, 0, true, false, h->num_cus, s);
     if (rc != MOE_OK) return rc;
-    return launch_topk(logits, T, c.E, c.k, c.renormalize, idx, w, s);
+    return launch_topk(logits, T, c.E, c.k, c.renormalize, idx, w, s, split, parts, p.split_stride);
 }
 
 // scale bytes of one expert's [rows, cols] matrix in the 4-bit layout: 16 per row and 512 columns
@@ -590,7 +606,12 @@ int moe_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *g
         if (rc != MOE_OK) return rc;
         logits = at<float>(workspace, ws_layout(h->cfg).logits);
     }
-    return do_gate_topk(h, x, wg, gate_bias, T, logits, topk_idx, topk_w, (hipStream_t)stream);
+    // the split-K slices of a small batch's gate GEMM live in the workspace; without one the GEMM runs whole
+    const WsLayout L = ws_layout(h->cfg);
+    float *parts = (workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0 && workspace_bytes >= L.total)
+                       ? at<float>(workspace, L.gate_parts)
+                       : nullptr;
+    return do_gate_topk(h, x, wg, gate_bias, T, logits, topk_idx, topk_w, (hipStream_t)stream, parts);
 }
 
 int moe_route_counts(moe_handle_t *h, const int32_t *topk_idx, int32_t T, int32_t *counts, int32_t *offsets,
@@ -705,7 +726,7 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
 
     if (empty) return launch_route(idx, 0, c.E, c.k, counts, offsets, dst_row, src_tok,
                                    at<int32_t>(workspace, L.block_hist), s);
-    rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s);
+    rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s, at<float>(workspace, L.gate_parts));
     if (rc != MOE_OK) return rc;
     // the routing step's scan kernel also writes the first expert GEMM's tile map (not when the
     // experts are buffered: their tile maps are per stage)

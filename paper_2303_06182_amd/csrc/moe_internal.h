@@ -107,6 +107,11 @@ struct GemmParams {
     void *C;             // [rows, N]
     int64_t ldc;
     int M, N, K;
+    // plain mode, fp32 C: K cut into k_split ranges (0 / 1 = whole K); range 0 writes C, range i > 0 writes
+    // c_parts + (i - 1) * split_stride (same ldc)
+    int k_split;
+    int64_t split_stride;
+    float *c_parts;
     // grouped mode
     const int32_t *offsets;      // [E+1]
     const int32_t *tile_expert;  // [max_m_tiles]
@@ -146,7 +151,8 @@ int launch_tile_map(const int32_t *offsets, int E, int block_m, int32_t *tile_ex
                     int32_t *num_tiles, int max_m_tiles, const int32_t *stage_of, int stage, hipStream_t s);
 
 // ---- routing -------------------------------------------------------------------------------------
-int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s);
+int launch_topk(float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s, int n_parts = 1,
+                const float *parts = nullptr, int64_t part_stride = 0);
 // block_hist: scratch of route_blocks(T)*E int32
 int route_blocks(int T);
 int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,

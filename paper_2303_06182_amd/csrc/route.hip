@@ -11,6 +11,7 @@ namespace moe355 {
 
 static constexpr int kThreads = 256;
 static constexpr int kWave = 64;
+static constexpr int kMaxLogitParts = 16;  // slices the top-k kernel can add up (the gate GEMM's split K)
 
 // ------------------------------------------------------------------------------------------------
 // softmax + top-k.  G lanes (a power of two <= 64) share one token; lane `sub` holds logits
@@ -22,9 +23,13 @@ static constexpr int kWave = 64;
 // multiple of 4), so every lane has V/4 float4 loads in flight; slot i of the lane is expert
 // (i/4)*4G + 4*sub + i%4, still ascending with i.
 template <int G, int V, bool VEC>
-__global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
-                                                        int renorm, int32_t *__restrict__ idx,
-                                                        float *__restrict__ w)
+// n_parts > 1: the logits arrive as n_parts partial sums (the gate GEMM's split K): slice 0 at `logits`,
+// slice i > 0 at parts + (i - 1) * part_stride; they are added in slice order and the sum is written
+// back to `logits`.
+__global__ __launch_bounds__(kThreads) void topk_kernel(float *logits, int T, int E, int k, int renorm,
+                                                        int32_t *__restrict__ idx, float *__restrict__ w,
+                                                        int n_parts, const float *__restrict__ parts,
+                                                        int64_t part_stride)
 {
     constexpr int TOK_PER_BLOCK = kThreads / G;
     const int sub = threadIdx.x % G;
@@ -39,7 +44,28 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
         for (int q = 0; q < V / 4; ++q) {
             const int e0 = (q * G + sub) * 4;
             float4 f = make_float4(NEG_INF, NEG_INF, NEG_INF, NEG_INF);
-            if (live && e0 < E) f = *reinterpret_cast<const float4 *>(logits + (int64_t)t * E + e0);
+            if (live && e0 < E) {
+                float *src = logits + (int64_t)t * E + e0;
+                f = *reinterpret_cast<const float4 *>(src);
+                if (n_parts > 1) {  // uniform over the grid; all slices are requested before the first is added
+                    float4 g[kMaxLogitParts - 1];
+#pragma unroll
+                    for (int sp = 1; sp < kMaxLogitParts; ++sp)
+                        g[sp - 1] = sp < n_parts ? *reinterpret_cast<const float4 *>(parts + (sp - 1) * part_stride +
+                                                                                     (int64_t)t * E + e0)
+                                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int sp = 1; sp < kMaxLogitParts; ++sp) {
+                        if (sp < n_parts) {
+                            f.x += g[sp - 1].x;
+                            f.y += g[sp - 1].y;
+                            f.z += g[sp - 1].z;
+                            f.w += g[sp - 1].w;
+                        }
+                    }
+                    *reinterpret_cast<float4 *>(src) = f;
+                }
+            }
             v[(4 * q + 0) % V] = f.x;
             v[(4 * q + 1) % V] = f.y;
             v[(4 * q + 2) % V] = f.z;
@@ -49,7 +75,22 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             const int e = sub + i * G;
-            v[i] = (live && e < E) ? logits[(int64_t)t * E + e] : NEG_INF;
+            v[i] = NEG_INF;
+            if (live && e < E) {
+                float *src = logits + (int64_t)t * E + e;
+                float f = *src;
+                if (n_parts > 1) {
+                    float g[kMaxLogitParts - 1];
+#pragma unroll
+                    for (int sp = 1; sp < kMaxLogitParts; ++sp)
+                        g[sp - 1] = sp < n_parts ? parts[(sp - 1) * part_stride + (int64_t)t * E + e] : 0.f;
+#pragma unroll
+                    for (int sp = 1; sp < kMaxLogitParts; ++sp)
+                        if (sp < n_parts) f += g[sp - 1];
+                    *src = f;
+                }
+                v[i] = f;
+            }
         }
     }
     uint32_t taken = 0;  // bit i: register slot i already selected (or beyond E)
@@ -126,39 +167,44 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const float *__restrict_
 }
 
 template <int G, int V, bool VEC>
-static int launch_topk_t(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w,
-                         hipStream_t s)
+static int launch_topk_t(float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s,
+                         int n_parts, const float *parts, int64_t part_stride)
 {
     const int tpb = kThreads / G;
     ProfScope ps("topk", s);
     hipLaunchKernelGGL((topk_kernel<G, V, VEC>), dim3(ceil_div(T, tpb)), dim3(kThreads), 0, s, logits, T, E, k, renorm,
-                       idx, w);
+                       idx, w, n_parts, parts, part_stride);
     MOE_LAUNCH_CHECK("topk_kernel");
     return MOE_OK;
 }
 
-int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s)
+int launch_topk(float *logits, int T, int E, int k, int renorm, int32_t *idx, float *w, hipStream_t s, int n_parts,
+                const float *parts, int64_t part_stride)
 {
     if (T == 0) return MOE_OK;
-    if (E % 4 == 0) {  // rows are 16-byte aligned: vector loads, fewer lanes per token
-        if (E <= 8) return launch_topk_t<2, 4, true>(logits, T, E, k, renorm, idx, w, s);
-        if (E <= 16) return launch_topk_t<4, 4, true>(logits, T, E, k, renorm, idx, w, s);
-        if (E <= 32) return launch_topk_t<8, 4, true>(logits, T, E, k, renorm, idx, w, s);
-        if (E <= 64) return launch_topk_t<16, 4, true>(logits, T, E, k, renorm, idx, w, s);
-        if (E <= 128) return launch_topk_t<16, 8, true>(logits, T, E, k, renorm, idx, w, s);
-        if (E <= 256) return launch_topk_t<16, 16, true>(logits, T, E, k, renorm, idx, w, s);
-        if (E <= 512) return launch_topk_t<32, 16, true>(logits, T, E, k, renorm, idx, w, s);
-        return launch_topk_t<64, 16, true>(logits, T, E, k, renorm, idx, w, s);
+    if (n_parts > kMaxLogitParts) {
+        set_error("top-k: %d logit slices, at most %d", n_parts, kMaxLogitParts);
+        return MOE_ERR_INVALID_ARG;
     }
-    if (E <= 4) return launch_topk_t<4, 1, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 8) return launch_topk_t<8, 1, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 16) return launch_topk_t<16, 1, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 32) return launch_topk_t<32, 1, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 64) return launch_topk_t<64, 1, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 128) return launch_topk_t<64, 2, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 256) return launch_topk_t<64, 4, false>(logits, T, E, k, renorm, idx, w, s);
-    if (E <= 512) return launch_topk_t<64, 8, false>(logits, T, E, k, renorm, idx, w, s);
-    return launch_topk_t<64, 16, false>(logits, T, E, k, renorm, idx, w, s);
+    if (E % 4 == 0) {  // rows are 16-byte aligned: vector loads, fewer lanes per token
+        if (E <= 8) return launch_topk_t<2, 4, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        if (E <= 16) return launch_topk_t<4, 4, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        if (E <= 32) return launch_topk_t<8, 4, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        if (E <= 64) return launch_topk_t<16, 4, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        if (E <= 128) return launch_topk_t<16, 8, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        if (E <= 256) return launch_topk_t<16, 16, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        if (E <= 512) return launch_topk_t<32, 16, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+        return launch_topk_t<64, 16, true>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    }
+    if (E <= 4) return launch_topk_t<4, 1, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 8) return launch_topk_t<8, 1, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 16) return launch_topk_t<16, 1, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 32) return launch_topk_t<32, 1, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 64) return launch_topk_t<64, 1, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 128) return launch_topk_t<64, 2, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 256) return launch_topk_t<64, 4, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    if (E <= 512) return launch_topk_t<64, 8, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
+    return launch_topk_t<64, 16, false>(logits, T, E, k, renorm, idx, w, s, n_parts, parts, part_stride);
 }
 
 // ------------------------------------------------------------------------------------------------

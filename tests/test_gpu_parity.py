@@ -77,6 +77,10 @@ GATE_CASES = [
     ("bf16_e16_k1", "bf16", 513, 72, 16, 1, True, 0.0, 30.0),
     ("bf16_e1000_k8", "bf16", 70, 64, 1000, 8, True, 0.0, 100.0),
     ("bf16_e3_k3", "bf16", 64, 64, 3, 3, True, 0.0, 100.0),
+    # few tokens, long K: the gate GEMM is cut along K into slices that the top-k kernel adds up
+    ("bf16_splitk_e128", "bf16", 100, 1024, 128, 2, True, 0.0, 30.0),
+    ("bf16_splitk_e37", "bf16", 33, 2048, 37, 3, False, 0.0, 30.0),
+    ("bf16_splitk_t1", "bf16", 1, 4096, 16, 2, True, 0.0, 30.0),
 ]
 
 
