@@ -950,7 +950,10 @@ int gemm_bf16_variant_w8(int64_t n_rows, int E)
 
 // 4-bit weights: 43 = 32x256, 48 = 64x256, four LDS stages each.  (Measured on 128 experts of 2048 x 8192
 // with 1 to 64 rows each: 256 columns per tile beat 128 by 25-30 % -- the A tile, re-read once per column
-// tile, weighs as much as a 128-column B tile at 4 bits -- and 512 lost again; 3, 4 and 6 stages +-5 %.)
+// tile, weighs as much as a 128-column B tile at 4 bits -- and 512 lost again; 3, 4 and 6 stages +-5 %.
+// With 8 or 16 tokens the second GEMM has fewer tiles than CUs and its time is the K loop of one tile,
+// 128 K tiles at about 0.65 us each, whatever the tile width or pipeline depth: only a split along K
+// would shorten it.)
 int gemm_bf16_variant_w4(int64_t n_rows, int E)
 {
     static int forced = -1;
