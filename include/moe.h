@@ -306,6 +306,19 @@ typedef struct moe_expert_cache moe_expert_cache_t;
 int64_t moe_expert_cache_bytes(const moe_handle_t *h, int32_t slots);
 int moe_expert_cache_create(moe_handle_t *h, int32_t slots, const void *host_w1, const void *host_w2,
                             void *device_mem, int64_t device_bytes, moe_expert_cache_t **out);
+/* The same buffer over quantised expert weights (the 8- and 4-bit formats further up; not in the
+ * paper, which buffers the parameters as they are): the host link carries half / a quarter of the
+ * bytes per missed expert.  wbits = 8: host_w1 / host_w2 are the e4m3 bytes of moe_quantize_e4m3
+ * (E * F * D each), w1_scale / w2_scale its fp32 scales [E]; wbits = 4: the e2m1 bytes of
+ * moe_quantize_mxfp4 (E * F * D / 2 each) and its block scale bytes.  The scales of ALL experts stay
+ * in DEVICE memory (w1_scale, w2_scale: device pointers, valid while the cache lives; they are at
+ * most 1/16 of the data); only the data bytes are buffered.  wbits = 0: as moe_expert_cache_create
+ * (scales NULL).  Needs what the quantised calls need (MOE_ERR_UNSUPPORTED otherwise).
+ * moe_layer_forward_buffered then runs the quantised expert GEMMs. */
+int64_t moe_expert_cache_bytes_q(const moe_handle_t *h, int32_t slots, int32_t wbits);
+int moe_expert_cache_create_q(moe_handle_t *h, int32_t slots, int32_t wbits, const void *host_w1, const void *host_w2,
+                              const void *w1_scale, const void *w2_scale, void *device_mem, int64_t device_bytes,
+                              moe_expert_cache_t **out);
 int moe_expert_cache_destroy(moe_expert_cache_t *c);
 int moe_expert_cache_reset(moe_expert_cache_t *c); /* forget every resident expert, zero the statistics */
 /* hits, misses, bytes copied host to device, and stages executed, since creation or reset */

@@ -37,6 +37,7 @@ EXPORTS = [
     "moe_placement_greedy", "moe_placement_anticorrelation", "moe_placement_loads",
     "moe_quantize_e4m3", "moe_expert_ffn_w8", "moe_layer_forward_w8",
     "moe_mxfp4_scale_bytes", "moe_quantize_mxfp4", "moe_expert_ffn_w4", "moe_layer_forward_w4",
+    "moe_expert_cache_bytes_q", "moe_expert_cache_create_q",
 ]
 
 
@@ -150,6 +151,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_forward_w4.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting),
                                          vp, i64, vp]
     lib.moe_layer_forward_w4.restype = ctypes.c_int
+    lib.moe_expert_cache_bytes_q.argtypes = [vp, i32, i32]
+    lib.moe_expert_cache_bytes_q.restype = i64
+    lib.moe_expert_cache_create_q.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i64, ctypes.POINTER(vp)]
+    lib.moe_expert_cache_create_q.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -421,20 +426,25 @@ class ExpertCache:
     """moe_expert_cache_*: `slots` device slots in front of expert parameters kept in pinned host
     memory (host_w1 [E,F,D], host_w2 [E,D,F], torch CPU tensors with pin_memory)."""
 
-    def __init__(self, layer: "MoeLayer", slots: int, host_w1: torch.Tensor, host_w2: torch.Tensor):
+    def __init__(self, layer: "MoeLayer", slots: int, host_w1: torch.Tensor, host_w2: torch.Tensor, wbits: int = 0,
+                 w1_scale: Optional[torch.Tensor] = None, w2_scale: Optional[torch.Tensor] = None):
+        """wbits = 8 / 4: host_w1 / host_w2 hold the quantised bytes (moe_quantize_e4m3 / moe_quantize_mxfp4,
+        copied to pinned host memory), w1_scale / w2_scale their scales, which stay on the device."""
         self.lib = layer.lib
         self.layer = layer
         self.slots = slots
         if host_w1.device.type != "cpu" or host_w2.device.type != "cpu":
             raise ValueError("host_w1 / host_w2 must be CPU tensors (pinned)")
         self.host_w1, self.host_w2 = host_w1, host_w2  # kept alive
-        nbytes = int(self.lib.moe_expert_cache_bytes(layer.h, slots))
+        self.w1_scale, self.w2_scale = w1_scale, w2_scale
+        nbytes = int(self.lib.moe_expert_cache_bytes_q(layer.h, slots, wbits))
         if nbytes < 0:
             _check(nbytes)
         self.device_mem = torch.empty(nbytes, dtype=torch.uint8, device=layer.device)
         self.c = ctypes.c_void_p()
-        _check(self.lib.moe_expert_cache_create(layer.h, slots, host_w1.data_ptr(), host_w2.data_ptr(),
-                                                _ptr(self.device_mem), nbytes, ctypes.byref(self.c)))
+        _check(self.lib.moe_expert_cache_create_q(layer.h, slots, wbits, host_w1.data_ptr(), host_w2.data_ptr(),
+                                                  _ptr(w1_scale), _ptr(w2_scale), _ptr(self.device_mem), nbytes,
+                                                  ctypes.byref(self.c)))
 
     def __del__(self):
         if getattr(self, "c", None) is not None and self.c:

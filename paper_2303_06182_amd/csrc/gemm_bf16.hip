@@ -532,7 +532,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 // one instruction = 1 KB = 32 rows of 32 bytes: lane L lands in row (L >> 1), 16-byte half
                 // (L & 1); in memory that 1 KB block is contiguous and the blocks of a 32-row group follow
                 // each other along K (the quantiser's layout)
-                const uint8_t *Bg4 = reinterpret_cast<const uint8_t *>(Bg0) + (int64_t)ti.expert * p.strideB;
+                const uint8_t *Bg4 = reinterpret_cast<const uint8_t *>(Bg0) +
+                                     (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
                 const int group_bytes = (K / BK) * 1024;
                 const int last_group = p.N / 32 - 1;
 #pragma unroll

@@ -448,6 +448,8 @@ struct moe_expert_cache {
     int slots = 0;
     const uint8_t *host_w1 = nullptr, *host_w2 = nullptr;
     int64_t half_bytes = 0;        // one expert's W1 (= W2) in bytes
+    int wbits = 0;                 // 0: elem weights; 8 / 4: e4m3 bytes / e2m1 nibbles in the host arrays and slots
+    const void *scale1 = nullptr, *scale2 = nullptr;  // device, all experts: fp32 [E] (8) or block scale bytes (4)
     uint8_t *d_slots = nullptr;    // [slots][W1 | W2]
     int32_t *d_slot_of = nullptr;  // [E] slot an active expert runs from
     int32_t *d_stage = nullptr;    // [E] launch it runs in (2 * stage + missed), -1 idle
@@ -731,7 +733,7 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
     // the routing step's scan kernel also writes the first expert GEMM's tile map (not when the
     // experts are buffered: their tile maps are per stage)
     const int64_t n_rows = (int64_t)T * c.k;
-    const int wbits = w1_blk ? 4 : w1_scale ? 8 : 0;
+    const int wbits = cache ? cache->wbits : (w1_blk ? 4 : w1_scale ? 8 : 0);
     const int bm1 = cache ? 0
                           : gemm_variant_block_m(c.dtype, wbits ? quant_variant(wbits, n_rows, c.E)
                                                                 : gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus));
@@ -913,30 +915,51 @@ int moe_layer_forward_w4(moe_handle_t *h, const void *x, const void *wg, const f
 }
 
 // ---- expert buffering ------------------------------------------------------------------------
-int64_t moe_expert_cache_bytes(const moe_handle_t *h, int32_t slots)
+// bytes of one expert's W1 (= W2) as the cache stores it
+static int64_t cache_half_bytes(const moe_config_t &c, int wbits)
+{
+    const int64_t n = (int64_t)c.F * c.D;
+    return wbits == 8 ? n : wbits == 4 ? n / 2 : n * elem_size(c.dtype);
+}
+
+int64_t moe_expert_cache_bytes_q(const moe_handle_t *h, int32_t slots, int32_t wbits)
 {
     g_err[0] = 0;
-    if (!h || slots < 1) {
-        set_error("handle is NULL or slots = %d < 1", slots);
+    if (!h || slots < 1 || (wbits != 0 && wbits != 8 && wbits != 4)) {
+        set_error("handle is NULL, slots = %d < 1 or wbits = %d not 0, 8 or 4", slots, wbits);
         return MOE_ERR_INVALID_ARG;
     }
     const moe_config_t &c = h->cfg;
-    return 2 * cache_index_bytes(c) + (int64_t)slots * 2 * c.F * c.D * elem_size(c.dtype);
+    return 2 * cache_index_bytes(c) + (int64_t)slots * 2 * cache_half_bytes(c, wbits);
 }
+
+int64_t moe_expert_cache_bytes(const moe_handle_t *h, int32_t slots) { return moe_expert_cache_bytes_q(h, slots, 0); }
 
 int moe_expert_cache_create(moe_handle_t *h, int32_t slots, const void *host_w1, const void *host_w2,
                             void *device_mem, int64_t device_bytes, moe_expert_cache_t **out)
 {
+    return moe_expert_cache_create_q(h, slots, 0, host_w1, host_w2, nullptr, nullptr, device_mem, device_bytes, out);
+}
+
+int moe_expert_cache_create_q(moe_handle_t *h, int32_t slots, int32_t wbits, const void *host_w1, const void *host_w2,
+                              const void *w1_scale, const void *w2_scale, void *device_mem, int64_t device_bytes,
+                              moe_expert_cache_t **out)
+{
     g_err[0] = 0;
-    if (!h || !out || slots < 1) {
-        set_error("expert cache: handle or out is NULL, or slots = %d < 1", slots);
+    if (!h || !out || slots < 1 || (wbits != 0 && wbits != 8 && wbits != 4)) {
+        set_error("expert cache: handle or out is NULL, slots = %d < 1 or wbits = %d not 0, 8 or 4", slots, wbits);
         return MOE_ERR_INVALID_ARG;
+    }
+    if (wbits != 0) {
+        const int rq = check_w8(h);
+        if (rq != MOE_OK) return rq;
+        if (bad_ptr(w1_scale, "w1_scale") || bad_ptr(w2_scale, "w2_scale")) return MOE_ERR_INVALID_ARG;
     }
     if (bad_ptr(host_w1, "host_w1") || bad_ptr(host_w2, "host_w2") || bad_ptr(device_mem, "device_mem"))
         return MOE_ERR_INVALID_ARG;
-    if (((uintptr_t)device_mem & 255) != 0 || device_bytes < moe_expert_cache_bytes(h, slots)) {
+    if (((uintptr_t)device_mem & 255) != 0 || device_bytes < moe_expert_cache_bytes_q(h, slots, wbits)) {
         set_error("expert cache: device_mem must be 256-byte aligned and hold %lld bytes (got %lld)",
-                  (long long)moe_expert_cache_bytes(h, slots), (long long)device_bytes);
+                  (long long)moe_expert_cache_bytes_q(h, slots, wbits), (long long)device_bytes);
         return MOE_ERR_WORKSPACE;
     }
     const moe_config_t &c = h->cfg;
@@ -949,7 +972,10 @@ int moe_expert_cache_create(moe_handle_t *h, int32_t slots, const void *host_w1,
     k->slots = slots;
     k->host_w1 = static_cast<const uint8_t *>(host_w1);
     k->host_w2 = static_cast<const uint8_t *>(host_w2);
-    k->half_bytes = (int64_t)c.F * c.D * elem_size(c.dtype);
+    k->half_bytes = cache_half_bytes(c, wbits);
+    k->wbits = wbits;
+    k->scale1 = w1_scale;
+    k->scale2 = w2_scale;
     uint8_t *base = static_cast<uint8_t *>(device_mem);
     k->d_slot_of = reinterpret_cast<int32_t *>(base);
     k->d_stage = reinterpret_cast<int32_t *>(base + cache_index_bytes(c));
@@ -1046,7 +1072,15 @@ static int buffered_expert_ffn(moe_handle_t *h, moe_expert_cache_t *k, const voi
     ex.a_rows = a_rows;
     ex.b_slot = k->d_slot_of;
     ex.stage_of = k->d_stage;
-    ex.slot_stride = 2 * (int64_t)c.F * c.D;
+    // stride between slots in the GEMM's unit for B: elements for elem weights, bytes for 8 and 4 bits
+    ex.slot_stride = k->wbits ? 2 * k->half_bytes : 2 * (int64_t)c.F * c.D;
+    if (k->wbits == 8) {
+        ex.w1_scale = static_cast<const float *>(k->scale1);
+        ex.w2_scale = static_cast<const float *>(k->scale2);
+    } else if (k->wbits == 4) {
+        ex.w1_blk = static_cast<const uint8_t *>(k->scale1);
+        ex.w2_blk = static_cast<const uint8_t *>(k->scale2);
+    }
     const void *w1 = k->d_slots, *w2 = k->d_slots + k->half_bytes;
     hipEvent_t last_done = nullptr;
     size_t ev = 0;

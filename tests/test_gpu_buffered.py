@@ -98,3 +98,48 @@ def test_buffered_empty_batch_and_errors(dev):
             binding._stream()))
     with pytest.raises(binding.MoeError):
         binding.ExpertCache(layer, 0, inp["w1"].pin_memory(), inp["w2"].pin_memory())
+
+
+@pytest.mark.parametrize("wbits", [8, 4])
+def test_buffered_quantised_weights_equal_the_resident_call(dev, wbits):
+    """The cache over e4m3 / e2m1 expert weights: bit for bit the result of moe_layer_forward_w8 / _w4
+    with all experts resident (itself checked against the oracle elsewhere), the oracle's hit / miss
+    counts, and half / a quarter of the bytes over the host link."""
+    w = wl.CONFIGS["mt_decoder"].scaled(name="buf_q%d" % wbits, T=48, D=256, F=512, E=32)
+    inp = wl.make_inputs(w, with_ffn_bias=True)
+    g = {k: (None if v is None else v.cuda()) for k, v in inp.items()}
+    xs = [x.cuda() for x in wl.decode_steps(w, 6, 0.8)]
+    layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
+    if wbits == 8:
+        q1, s1 = layer.moe_quantize_e4m3(g["w1"])
+        q2, s2 = layer.moe_quantize_e4m3(g["w2"])
+        fwd = layer.moe_layer_forward_w8
+    else:
+        q1, s1 = layer.moe_quantize_mxfp4(g["w1"])
+        q2, s2 = layer.moe_quantize_mxfp4(g["w2"])
+        fwd = layer.moe_layer_forward_w4
+    torch.cuda.synchronize()
+    hq1, hq2 = q1.cpu().pin_memory(), q2.cpu().pin_memory()
+    expert_bytes = 2 * w.F * w.D * wbits // 8
+    ref, trace = [], []
+    for x in xs:
+        r = layer.empty_routing(w.T)
+        y = fwd(x, g["wg"], q1, q2, s1, s2, g["gate_bias"], g["b1"], g["b2"], routing_out=r)
+        torch.cuda.synchronize()
+        ref.append(y.clone())
+        trace.append(np.nonzero(to_np(r["counts"]))[0].tolist())
+    # the device copies of the quantised weights are not needed any more: the cache must not depend on them
+    q1.fill_(0x7F)
+    q2.fill_(0x7F)
+    for slots in (4, 12, 32):
+        say("buffered q%d" % wbits, "slots", slots, "active per step", [len(t) for t in trace])
+        cache = binding.ExpertCache(layer, slots, hq1, hq2, wbits, s1, s2)
+        for i, x in enumerate(xs):
+            y = cache.moe_layer_forward_buffered(x, g["wg"], g["gate_bias"], g["b1"], g["b2"])
+            torch.cuda.synchronize()
+            assert torch.equal(y, ref[i]), "step %d, %d slots" % (i, slots)
+        sim = ec.simulate(trace, slots, "paper")
+        st = cache.stats()
+        assert (st["hits"], st["misses"]) == (sim["hits"], sim["misses"])
+        assert st["bytes_copied"] == sim["misses"] * expert_bytes
+        del cache
