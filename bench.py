@@ -206,10 +206,23 @@ def run_buffering(name, slots_list, n_steps, rho=0.9, tokens=(64, 16)):
     results = {}
     for T in tokens:  # the workload as defined, and a sparser step (a quarter of the tokens: about 3/4 of the experts idle)
         results["T%d" % T] = _buffering_runs(base.scaled(T=T), g, hw1, hw2, slots_list, n_steps, rho)
+    # the same buffer over quantised expert weights (not in the paper): fewer bytes per missed expert
+    del hw1, hw2
+    layer = binding.MoeLayer(base.T, base.D, base.F, base.E, base.k, base.dtype)
+    for label, wbits, quant in (("e4m3", 8, layer.moe_quantize_e4m3), ("mxfp4", 4, layer.moe_quantize_mxfp4)):
+        q1, s1 = quant(g["w1"])
+        q2, s2 = quant(g["w2"])
+        torch.cuda.synchronize()
+        fmt = dict(wbits=wbits, q1=q1, q2=q2, s1=s1, s2=s2)
+        hq1, hq2 = q1.cpu().pin_memory(), q2.cpu().pin_memory()
+        results["T%d_%s" % (tokens[0], label)] = _buffering_runs(base.scaled(T=tokens[0]), g, hq1, hq2, slots_list,
+                                                                 n_steps, rho, fmt)
+        del fmt, q1, q2, hq1, hq2
+        torch.cuda.empty_cache()
     return results
 
 
-def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho):
+def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho, fmt=None):
     import numpy as np
     import torch
     from oracle import expert_cache as ec
@@ -220,26 +233,37 @@ def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho):
     layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
     y = torch.empty((w.T, w.D), dtype=w.torch_dtype, device="cuda")
     routing = layer.empty_routing(w.T)
-    expert_bytes = 2 * w.F * w.D * (2 if w.dtype == "bf16" else 4)
+    wbits = fmt["wbits"] if fmt else 0
+    expert_bytes = 2 * w.F * w.D * wbits // 8 if fmt else 2 * w.F * w.D * (2 if w.dtype == "bf16" else 4)
+
+    def resident(x, **kw):
+        if not fmt:
+            layer.moe_layer_forward(x, g["wg"], g["w1"], g["w2"], g["gate_bias"], y=y, **kw)
+        elif wbits == 8:
+            layer.moe_layer_forward_w8(x, g["wg"], fmt["q1"], fmt["q2"], fmt["s1"], fmt["s2"], g["gate_bias"], y=y, **kw)
+        else:
+            layer.moe_layer_forward_w4(x, g["wg"], fmt["q1"], fmt["q2"], fmt["s1"], fmt["s2"], g["gate_bias"], y=y, **kw)
 
     trace = []
     for x in xs:  # plain call: warm-up and the activity trace
-        layer.moe_layer_forward(x, g["wg"], g["w1"], g["w2"], g["gate_bias"], y=y, routing_out=routing)
+        resident(x, routing_out=routing)
         trace.append(np.nonzero(routing["counts"].cpu().numpy())[0].tolist())
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for x in xs:
-        layer.moe_layer_forward(x, g["wg"], g["w1"], g["w2"], g["gate_bias"], y=y)
+        resident(x)
     torch.cuda.synchronize()
     plain_ms = (time.perf_counter() - t0) * 1e3 / n_steps
-    out = dict(workload=name, steps=n_steps, rho=rho, expert_bytes=expert_bytes,
+    out = dict(workload=name, weights="bf16" if not fmt else ("e4m3" if wbits == 8 else "mxfp4"), steps=n_steps, rho=rho,
+               expert_bytes=expert_bytes,
                active_experts_per_step=float(np.mean([len(t) for t in trace])),
                distinct_experts=len(set(e for t in trace for e in t)),
                all_resident=dict(ms_per_step=plain_ms, tokens_per_s=w.T / (plain_ms * 1e-3),
                                  expert_bytes_on_device=w.E * expert_bytes),
                slots={}, simulated_miss_rate={})
     for slots in slots_list:
-        cache = binding.ExpertCache(layer, slots, hw1, hw2)
+        cache = (binding.ExpertCache(layer, slots, hw1, hw2, wbits, fmt["s1"], fmt["s2"]) if fmt
+                 else binding.ExpertCache(layer, slots, hw1, hw2))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for x in xs:
