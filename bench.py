@@ -38,6 +38,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("skewed_large", "expert_gemm1"): 13396598 * 1024, ("skewed_large", "expert_gemm2"): 10831334 * 1024,
     ("skewed_large", "dispatch"): 788764 * 1024, ("skewed_large", "combine"): 791097 * 1024,
     ("skewed_large", "gate_gemm"): 299453 * 1024,
+    ("mt_encoder", "expert_gemm1"): 2706783 * 1024, ("mt_encoder", "expert_gemm2"): 2316562 * 1024,
     ("mt_decoder", "expert_gemm1"): (2 * 1328785 + 2048) * 1024, ("mt_decoder", "expert_gemm2"): (2 * 1330728 + 512) * 1024,
 }
 
