@@ -200,6 +200,14 @@ def test_layer_forward_w4_full_size_decoder(dev):
     torch.cuda.empty_cache()
 
 
+def test_layer_forward_w4_full_size_lm(dev):
+    """The headline workload's shape (64 experts, about 256 rows each): the 64-row tiles of the quantised path."""
+    w = wl.CONFIGS["lm"]
+    say("w4 full lm", w)
+    run_w4_layer(w, device="cuda", check_experts={0, 31, 63})
+    torch.cuda.empty_cache()
+
+
 def test_w4_argument_errors(dev):
     m = binding.MoeLayer(64, 72, 128, 4, 2, "bf16")      # D not a multiple of 64
     x = torch.zeros(8, 72, dtype=torch.bfloat16, device="cuda")
