@@ -410,18 +410,35 @@ def test_argument_errors(dev):
     torch.cuda.synchronize()
 
 
-def test_layer_forward_can_be_captured_in_a_graph(dev):
+@pytest.mark.parametrize("kind", ["bf16_mid", "bf16_decoder", "w8_decoder", "w4_decoder"])
+def test_layer_forward_can_be_captured_in_a_graph(dev, kind):
     """The fused call only enqueues kernels on the caller's stream (no allocation, no host wait,
     no memset node), so it can be recorded into a HIP graph; every replay, with eager work and
-    synchronisations in between, must reproduce the eager result bit for bit."""
-    w = wl.CONFIGS["lm"].scaled(name="graph", T=1500, D=256, F=512, E=16)
+    synchronisations in between, must reproduce the eager result bit for bit.  The decoder-sized
+    cases take the small-batch kernels (gate GEMM split along K, single-block routing) and the
+    quantised expert GEMMs through the same check."""
+    if kind == "bf16_mid":
+        w = wl.CONFIGS["lm"].scaled(name="graph", T=1500, D=256, F=512, E=16)
+    else:
+        w = wl.CONFIGS["mt_decoder"].scaled(name="graph_dec", D=512, F=1024, E=32)
     g = cuda(wl.make_inputs(w))
     m = layer_for(w)
     y_eager = torch.empty((w.T, w.D), dtype=torch.bfloat16, device="cuda")
     y_graph = torch.empty_like(y_eager)
+    if kind == "w8_decoder":
+        q1, s1 = m.moe_quantize_e4m3(g["w1"])
+        q2, s2 = m.moe_quantize_e4m3(g["w2"])
+    elif kind == "w4_decoder":
+        q1, s1 = m.moe_quantize_mxfp4(g["w1"])
+        q2, s2 = m.moe_quantize_mxfp4(g["w2"])
 
     def step(out):
-        m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"], y=out)
+        if kind == "w8_decoder":
+            m.moe_layer_forward_w8(g["x"], g["wg"], q1, q2, s1, s2, g["gate_bias"], y=out)
+        elif kind == "w4_decoder":
+            m.moe_layer_forward_w4(g["x"], g["wg"], q1, q2, s1, s2, g["gate_bias"], y=out)
+        else:
+            m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"], y=out)
 
     for _ in range(3):
         step(y_eager)
