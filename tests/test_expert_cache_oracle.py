@@ -131,3 +131,15 @@ def test_single_slot_and_empty_batches():
     assert ec.simulate([[], []], 2, "paper")["miss_rate"] == 0.0
     with pytest.raises(ValueError):
         ec.ExpertCache(0)
+
+
+def test_lru_and_fifo_by_hand():
+    """Two slots, batches (1), (2), (1), (3), (1).  LRU: 3 replaces 2, because 1 was used in the third
+    batch, and the last access of 1 hits.  FIFO: 3 replaces 1, the first to come in, and 1 then replaces 2."""
+    trace = [[1], [2], [1], [3], [1]]
+    lru = ec.simulate(trace, 2, "lru")
+    assert [l.victim for l in lru["loads"]] == [-1, -1, 2]
+    assert (lru["hits"], lru["misses"]) == (2, 3)
+    fifo = ec.simulate(trace, 2, "fifo")
+    assert [l.victim for l in fifo["loads"]] == [-1, -1, 1, 2]
+    assert (fifo["hits"], fifo["misses"]) == (1, 4)
