@@ -28,6 +28,11 @@ MUTATIONS = {
     "static_second_choice_first": ("for (int j = 0; j < k; ++j) {\n        for (int t = 0; t < T; ++t) {",
                                    "for (int j = k - 1; j >= 0; --j) {\n        for (int t = 0; t < T; ++t) {"),
     "static_capacity_off_by_one": ("if (fill[e] < capacity) {", "if (fill[e] <= capacity) {"),
+    "b1_dropped": ("acc += ld(b1, (size_t)e * F + f, dt);", "acc += 0.0;"),
+    "renormalisation_ignored": ("        if (renorm) {\n            for (int j = 0; j < k; ++j)", "        if (0) {\n            for (int j = 0; j < k; ++j)"),
+    "raw_softmax_renormalised": ("            for (int e = 0; e < E; ++e)\n                denom += exp((double)l[e] - m);",
+                                 "            for (int j = 0; j < k; ++j)\n                denom += exp((double)l[sel[j]] - m);"),
+    "w1_transposed": ("size_t base = ((size_t)e * F + f) * D;", "size_t base = ((size_t)e * F) * D + f;"),
 }
 
 
@@ -66,7 +71,10 @@ def pin_topk(lib):
     ref = np.array([sorted(range(E), key=lambda e: (-float(l[t, e]), e))[:k] for t in range(T)], np.int32)
     p = scipy.special.softmax(l.astype(np.float64), axis=1)
     p2 = np.take_along_axis(p, ref.astype(np.int64), 1)
-    return np.array_equal(idx, ref) and np.allclose(w, p2 / p2.sum(1, keepdims=True), rtol=1e-12)
+    ok = np.array_equal(idx, ref) and np.allclose(w, p2 / p2.sum(1, keepdims=True), rtol=1e-12)
+    # without renormalisation the weights are the softmax probabilities themselves
+    lib.moe_oracle_topk(P(l), T, E, k, 0, P(idx), P(w))
+    return ok and np.array_equal(idx, ref) and np.allclose(w, p2, rtol=1e-12)
 
 
 def pin_logits(lib):
@@ -122,6 +130,8 @@ CATCHES = {
     "offsets_off_by_one": pin_route, "rank_not_stable": pin_route,
     "relu_dropped": pin_layer, "w2_transposed": pin_layer, "gate_weight_dropped": pin_layer, "b2_dropped": pin_layer,
     "static_second_choice_first": pin_static, "static_capacity_off_by_one": pin_static,
+    "b1_dropped": pin_layer, "w1_transposed": pin_layer,
+    "renormalisation_ignored": pin_topk, "raw_softmax_renormalised": pin_topk,
 }
 
 
