@@ -223,3 +223,58 @@ def test_w4_argument_errors(dev):
     assert ei.value.code == binding.MOE_ERR_INVALID_ARG
     assert ok.lib.moe_mxfp4_scale_bytes(64, 640) == 2 * 2 * 512
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("fmt", ["w8", "w4"])
+def test_quantised_layer_T_zero_T_one_and_one_hot_routing(dev, fmt):
+    """Degenerate batches through the quantised calls: no token, one token, and every token on the
+    same two experts (all other experts idle, their weights poisoned)."""
+    from oracle import quant_e4m3 as o8
+    w = wl.CONFIGS["lm"].scaled(name="q_edge", T=300, D=128, F=256, E=8, k=2, gate_scale=1.0, zipf_s=0.0)
+    inp = wl.make_inputs(w, with_ffn_bias=True)
+    # a gate bias that decides the routing for every token: experts 5 and 2, in that order
+    gb = torch.zeros(w.E, dtype=torch.float32)
+    gb[5], gb[2] = 60.0, 40.0
+    g = {k: (None if v is None else v.cuda()) for k, v in inp.items()}
+    g["gate_bias"] = gb.cuda()
+    m = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, "bf16")
+    if fmt == "w8":
+        q1, s1 = m.moe_quantize_e4m3(g["w1"])
+        q2, s2 = m.moe_quantize_e4m3(g["w2"])
+        fwd, oqm = m.moe_layer_forward_w8, o8
+        deq = lambda t: torch.from_numpy(o8.dequantize(*o8.quantize(t.float().numpy().astype(np.float64))).astype(np.float32)).to(torch.bfloat16)
+        poison = 0x7F
+    else:
+        q1, s1 = m.moe_quantize_mxfp4(g["w1"])
+        q2, s2 = m.moe_quantize_mxfp4(g["w2"])
+        fwd = m.moe_layer_forward_w4
+        deq = lambda t: dequant_bf16(*oq.quantize(t.float().numpy().astype(np.float64)))
+        poison = 0x77
+    for e in range(w.E):
+        if e not in (2, 5):
+            q1[e] = poison
+            q2[e] = poison
+            if fmt == "w4":
+                s1[e] = 254
+                s2[e] = 254
+    w1r, w2r = deq(inp["w1"]), deq(inp["w2"])
+    for T in (0, 1, w.T):
+        x = g["x"][:T].contiguous()
+        r = m.empty_routing(T)
+        y = fwd(x, g["wg"], q1, q2, s1, s2, g["gate_bias"], g["b1"], g["b2"], routing_out=r)
+        torch.cuda.synchronize()
+        assert y.shape == (T, w.D)
+        if T == 0:
+            assert int(r["counts"].sum()) == 0
+            continue
+        ridx = np.tile(np.array([[5, 2]], dtype=np.int32), (T, 1))
+        np.testing.assert_array_equal(to_np(r["topk_idx"]), ridx)
+        assert to_np(r["counts"]).tolist() == [0, 0, T, 0, 0, T, 0, 0]
+        logits = orc.gate_logits(inp["x"][:T], inp["wg"], gb)
+        _, rw = orc.topk(logits, w.k, True)
+        ref = orc.layer_tokens(inp["x"][:T], w1r, w2r, ridx, rw, b1=inp["b1"], b2=inp["b2"])
+        got = to_np(y)
+        assert np.all(np.isfinite(got))
+        err = norm_max_err(got, ref)
+        say("  %s T=%d err=%.3e" % (fmt, T, err))
+        assert err <= TOL["bf16"], err
