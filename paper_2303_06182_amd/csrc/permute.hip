@@ -55,39 +55,60 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
 }
 
-template <bool BF16>
+// KC: compile-time bound of k (the loop over a token's rows is unrolled, so the index loads of all
+// the lane's work items go out first, then all row loads, and only then the arithmetic: two memory
+// latencies per lane instead of two per row).  The sum runs in slot order j = 0 .. k-1 whatever KC is.
+template <bool BF16, int KC>
 __global__ __launch_bounds__(kThreads) void combine_kernel(const uint4 *__restrict__ yp,
                                                            const int32_t *__restrict__ dst_row,
                                                            const float *__restrict__ w, int64_t total, int vpr,
                                                            int k, uint4 *__restrict__ y)
 {
     const int64_t base = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+    int64_t row[kUnroll][KC];
+    float gate[kUnroll][KC];
+    int col[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t v = base + (int64_t)u * kThreads;
+        const int64_t t = v < total ? v / vpr : 0;
+        col[u] = v < total ? (int)(v - t * vpr) : 0;
+#pragma unroll
+        for (int j = 0; j < KC; ++j) {
+            const bool on = v < total && j < k;
+            row[u][j] = on ? (int64_t)dst_row[t * k + j] : -1;  // a dropped assignment (static capacity) is -1 too
+            gate[u][j] = on ? w[t * k + j] : 0.f;
+        }
+    }
+    uint4 q[kUnroll][KC];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+        for (int j = 0; j < KC; ++j)
+            q[u][j] = row[u][j] >= 0 ? yp[row[u][j] * vpr + col[u]] : make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t v = base + (int64_t)u * kThreads;
         if (v >= total) continue;
-        const int64_t t = v / vpr;
-        const int c = (int)(v - t * vpr);
         float acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-        for (int j = 0; j < k; ++j) {
-            const int64_t r = dst_row[t * k + j];
-            if (r < 0) continue;  // an assignment dropped by a static capacity contributes nothing
-            const float g = w[t * k + j];
-            const uint4 q = yp[r * vpr + c];
+#pragma unroll
+        for (int j = 0; j < KC; ++j) {
+            if (row[u][j] < 0) continue;  // contributes nothing
+            const float g = gate[u][j];
             if (BF16) {
-                const uint32_t p[4] = {q.x, q.y, q.z, q.w};
+                const uint32_t p[4] = {q[u][j].x, q[u][j].y, q[u][j].z, q[u][j].w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     acc[2 * i] = fmaf(g, bf16_lo(p[i]), acc[2 * i]);
                     acc[2 * i + 1] = fmaf(g, bf16_hi(p[i]), acc[2 * i + 1]);
                 }
             } else {
-                acc[0] = fmaf(g, __uint_as_float(q.x), acc[0]);
-                acc[1] = fmaf(g, __uint_as_float(q.y), acc[1]);
-                acc[2] = fmaf(g, __uint_as_float(q.z), acc[2]);
-                acc[3] = fmaf(g, __uint_as_float(q.w), acc[3]);
+                acc[0] = fmaf(g, __uint_as_float(q[u][j].x), acc[0]);
+                acc[1] = fmaf(g, __uint_as_float(q[u][j].y), acc[1]);
+                acc[2] = fmaf(g, __uint_as_float(q[u][j].z), acc[2]);
+                acc[3] = fmaf(g, __uint_as_float(q[u][j].w), acc[3]);
             }
         }
         uint4 o;
@@ -129,12 +150,15 @@ int launch_combine(int dtype, const void *yp, const int32_t *dst_row, const floa
     const int64_t total = (int64_t)T * vpr;
     const int64_t blocks = (total + kThreads * kUnroll - 1) / (kThreads * kUnroll);
     ProfScope ps("combine", s);
-    if (dtype == MOE_DTYPE_BF16)
-        hipLaunchKernelGGL((combine_kernel<true>), dim3((unsigned)blocks), dim3(kThreads), 0, s, (const uint4 *)yp,
-                           dst_row, w, total, vpr, k, (uint4 *)y);
-    else
-        hipLaunchKernelGGL((combine_kernel<false>), dim3((unsigned)blocks), dim3(kThreads), 0, s, (const uint4 *)yp,
-                           dst_row, w, total, vpr, k, (uint4 *)y);
+#define MOE_COMBINE(BF, KC)                                                                                      \
+    hipLaunchKernelGGL((combine_kernel<BF, KC>), dim3((unsigned)blocks), dim3(kThreads), 0, s, (const uint4 *)yp, \
+                       dst_row, w, total, vpr, k, (uint4 *)y)
+    const bool bf = dtype == MOE_DTYPE_BF16;
+    if (k <= 1) { if (bf) MOE_COMBINE(true, 1); else MOE_COMBINE(false, 1); }
+    else if (k <= 2) { if (bf) MOE_COMBINE(true, 2); else MOE_COMBINE(false, 2); }
+    else if (k <= 4) { if (bf) MOE_COMBINE(true, 4); else MOE_COMBINE(false, 4); }
+    else { if (bf) MOE_COMBINE(true, MOE_MAX_K); else MOE_COMBINE(false, MOE_MAX_K); }
+#undef MOE_COMBINE
     MOE_LAUNCH_CHECK("combine_kernel");
     return MOE_OK;
 }
