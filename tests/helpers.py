@@ -24,6 +24,17 @@ def norm_max_err(got, ref) -> float:
     return float(np.abs(got - ref).max() / (denom if denom > 0 else 1.0))
 
 
+def p999_rel_err(got, ref) -> float:
+    """99.9th percentile of the per-element relative error over the elements that are not near a zero
+    crossing (|y_ref| > 1e-3 max|y_ref|): reported beside the normalised max error, never the gate."""
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    big = np.abs(ref) > 1e-3 * np.abs(ref).max()
+    if not big.any():
+        return 0.0
+    return float(np.percentile(np.abs(got[big] - ref[big]) / np.abs(ref[big]), 99.9))
+
+
 def to_np(t: torch.Tensor) -> np.ndarray:
     t = t.detach().cpu()
     if t.dtype == torch.bfloat16:

@@ -12,7 +12,7 @@ import torch
 
 from oracle import moe_oracle as orc
 from paper_2303_06182_amd import binding, workloads as wl
-from helpers import LOGIT_ATOL, LOGIT_RTOL, TOL, W_TOL, guarded_inputs, norm_max_err, to_np
+from helpers import LOGIT_ATOL, LOGIT_RTOL, TOL, W_TOL, guarded_inputs, norm_max_err, p999_rel_err, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -262,8 +262,8 @@ def run_layer_and_check(w: wl.Workload, sample=None, with_ffn_bias=False, renorm
     assert np.all(np.isfinite(got))
     got_rows = got if tokens is None else got[tokens]
     err = norm_max_err(got_rows, ref_y)
-    say("  %s: T=%d redraws=%d max share=%.3f idle experts=%d  err=%.3e" %
-        (w.name, w.T, redraws, rc.max() / rc.sum(), int((rc == 0).sum()), err))
+    say("  %s: T=%d redraws=%d max share=%.3f idle experts=%d  err=%.3e  99.9th pct rel err=%.3e" %
+        (w.name, w.T, redraws, rc.max() / rc.sum(), int((rc == 0).sum()), err, p999_rel_err(got_rows, ref_y)))
     assert err <= TOL[w.dtype], err
     return dict(err=err, counts=rc, y=y, routing=r)
 
