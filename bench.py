@@ -347,6 +347,41 @@ def run_weight_formats(name, steps=20, warmup=4, profile_steps=5):
     return out
 
 
+def yardsticks():
+    """What the box itself reaches, measured in the same process: a plain device-to-device copy (HBM
+    read + write) and the vendor library's dense bf16 GEMM on the two expert-GEMM shapes of mt_encoder.
+    Context for the roofline fractions, which stay quoted against the nominal peaks."""
+    import torch
+    out = {}
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    out["copy_GBps"] = 20 * 2 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+    del src, dst
+    gemms = {}
+    for label, (M, K, N) in (("32768x2048x8192", (32768, 2048, 8192)), ("32768x8192x2048", (32768, 8192, 2048))):
+        a = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
+        b = torch.randn(N, K, device="cuda", dtype=torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(a, b.t())
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            torch.matmul(a, b.t())
+        torch.cuda.synchronize()
+        gemms[label] = 10 * 2.0 * M * K * N / (time.perf_counter() - t0) / 1e12
+        del a, b
+    out["vendor_bf16_gemm_TFLOPs"] = gemms
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(name, inp, budget_tokens):
     """The CPU oracle as it stands, timed on the host cores on a bounded sample of the same
     workload: the gate, top-k and routing for every token, the expert FFN and combine for
@@ -384,6 +419,7 @@ def main():
     ap.add_argument("--no-static", action="store_true", help="skip the static-capacity baseline runs")
     ap.add_argument("--no-buffering", action="store_true", help="skip the expert-buffering runs")
     ap.add_argument("--no-w8", action="store_true", help="skip the run with 8- and 4-bit expert weights (mt_decoder)")
+    ap.add_argument("--no-yardsticks", action="store_true", help="skip the box's own copy bandwidth and vendor GEMM rate")
     ap.add_argument("--buffering-steps", type=int, default=16, help="decode steps of the expert-buffering runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write elementwise kernel three times (untimed): gives counter runs "
@@ -429,6 +465,7 @@ def main():
     if not args.no_buffering:
         buffering = run_buffering("mt_decoder", [16, 48, 96], args.buffering_steps)
     w8 = None if args.no_w8 else run_weight_formats("mt_decoder")
+    yard = None if args.no_yardsticks else yardsticks()
     cpu = cpu_baseline(args.config, main_res["host"], args.cpu_tokens) if args.cpu_tokens > 0 else None
 
     dom = dict(main_res["dominant"])
@@ -457,6 +494,7 @@ def main():
         "static_baseline": static,
         "expert_buffering": buffering,
         "weight_formats": w8,
+        "yardsticks": yard,
         "paper_context": "paper reports only relative whole-model speedups of dynamic over static gating on "
                          "8xV100 nodes (LM 6.21-11.23x, MT encoder 5.75-10.98x, MT decoder 2.58-5.71x); "
                          "no absolute number exists for this metric",
