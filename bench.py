@@ -108,6 +108,20 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
     ms_per_step = max(wall_ms, ev_ms) / steps
     counts = routing["counts"].cpu().numpy()
 
+    # the spread behind the mean: the same steps again, each between an event pair of its own
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in pairs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    each = sorted(a.elapsed_time(b) for a, b in pairs)
+    step_ms = dict(median=each[len(each) // 2], min=each[0], max=each[-1], n=len(each))
+    # bytes one step must touch (expert weights with rows + activations): against the 256 MB last-level
+    # cache this says whether a step can find its weights cached from the step before
+    es = 2 if w.dtype == "bf16" else 4
+    working_set = int((counts > 0).sum()) * 2 * w.D * w.F * es + w.T * w.k * (2 * w.D + w.F) * es
+
     # per-kernel durations: HIP events recorded by the library around every launch, on the same stream
     acc = {}
     for _ in range(profile_steps):
@@ -138,7 +152,8 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
             kernels[kname]["in_fused_call"] = False  # measured through its own entry point, not part of ms_per_step
     dominant = max((r for r in kernels.values() if r.get("in_fused_call", True)), key=lambda r: r["avg_ms"])
     res = dict(workload=name, T=w.T, D=w.D, F=w.F, E=w.E, k=w.k, dtype=w.dtype,
-               ms_per_step=ms_per_step, tokens_per_s=w.T / (ms_per_step * 1e-3),
+               ms_per_step=ms_per_step, tokens_per_s=w.T / (ms_per_step * 1e-3), step_ms=step_ms,
+               working_set_bytes=working_set,
                max_expert_share=float(counts.max() / counts.sum()), idle_experts=int((counts == 0).sum()),
                workspace_bytes=layer.workspace_bytes, dominant=dominant, kernels=kernels, host=host)
     del layer, inp, y, routing
@@ -451,7 +466,8 @@ def main():
     also = {}
     for name in [a for a in args.also.split(",") if a and a != args.config]:
         r = run_config(name, max(5, args.steps // 5), max(2, args.warmup // 5), profile_steps=5)
-        also[name] = dict(tokens_per_s=r["tokens_per_s"], ms_per_step=r["ms_per_step"], roofline=r["dominant"],
+        also[name] = dict(tokens_per_s=r["tokens_per_s"], ms_per_step=r["ms_per_step"], step_ms=r["step_ms"],
+                          working_set_bytes=r["working_set_bytes"], roofline=r["dominant"],
                           kernels={k: dict(avg_ms=v["avg_ms"], bound=v["bound"], frac=v["frac"])
                                    for k, v in r["kernels"].items()},
                           max_expert_share=r["max_expert_share"])
@@ -477,6 +493,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"],
+        "step_ms": main_res["step_ms"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -484,7 +501,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.config, "T": main_res["T"], "D": main_res["D"], "F": main_res["F"],
                    "E": main_res["E"], "k": main_res["k"], "max_expert_share": main_res["max_expert_share"],
-                   "idle_experts": main_res["idle_experts"], "workspace_bytes": main_res["workspace_bytes"]},
+                   "idle_experts": main_res["idle_experts"], "workspace_bytes": main_res["workspace_bytes"],
+                   "working_set_bytes": main_res["working_set_bytes"]},
         "roofline": {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "avg_ms",
                                                 "algorithmic_bytes", "algorithmic_flops")},
         "cpu_baseline": cpu,
