@@ -424,8 +424,8 @@ def cpu_baseline(name, inp, budget_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="lm")
     ap.add_argument("--also", default="skewed_large,mt_encoder,mt_decoder,tiny_f32",
                     help="comma list of further workloads reported under 'also' (the static baseline runs only "
