@@ -55,6 +55,12 @@
 namespace moe355 {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+// Types for reading operand fragments out of LDS.  The compiler orders an LDS read that carries type-based
+// alias information after EVERY direct-to-LDS load in flight (s_waitcnt vmcnt(0) in front of the read), which
+// drains the load pipeline once per K tile; reads through vector types and may_alias types carry none, and
+// the explicit vmcnt before each stage barrier is what orders them.
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef uint32_t __attribute__((may_alias)) u32_lds;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
@@ -235,7 +241,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 const int bytepos = ((ks ^ ((lane >> 2) & 3)) << 4) + (frag_half << 3);
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
-                    const uint2 raw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint8_t *>(cB) +
+                    const u32x2 raw = *reinterpret_cast<const u32x2 *>(reinterpret_cast<const uint8_t *>(cB) +
                                                                        ni * 32 * (BK) + bytepos);
                     const f32x2 f0 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.x, false);
                     const f32x2 f1 = __builtin_amdgcn_cvt_pk_f32_fp8(raw.x, true);
@@ -251,8 +257,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 const int sb = ((kt & 7) << 1) + (ks >> 1);
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
-                    const uint32_t raw = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(cB) +
-                                                                             ni * 32 * (BK / 2) + ks * 8 + frag_half * 4);
+                    const uint32_t raw = *reinterpret_cast<const u32_lds *>(reinterpret_cast<const uint8_t *>(cB) +
+                                                                            ni * 32 * (BK / 2) + ks * 8 + frag_half * 4);
                     const uint32_t w4[4] = {sc_cur[ni].x, sc_cur[ni].y, sc_cur[ni].z, sc_cur[ni].w};
                     uint32_t word = w4[0];
 #pragma unroll
@@ -329,6 +335,18 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
 #pragma unroll
                     for (int i = 0; i < 4; ++i) bias32[ni][g][i] = (col + i < p.N) ? p.bias_f32[col + i] : 0.f;
                 }
+            // Added here, under the same condition as the loads and for every row block, not inside the
+            // row / column predicates below: a loaded register whose use sits behind a branch that a wave may
+            // skip counts as "load still in flight" for the rest of the kernel, and the compiler then waits
+            // for ALL loads (vmcnt(0)) before it reuses that register -- at the top of every K iteration.
+            if constexpr (!ACC_IN_AGPR) {
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[mi][ni][r] += bias32[ni][r >> 2][r & 3];
+            }
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -365,9 +383,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                 if (col + i < p.N) v[i] += from_bf16(bias[col + i]);
                         }
                     }
-                    if (add_bias32) {
+                    if constexpr (ACC_IN_AGPR) {
+                        if (add_bias32) {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] += bias32[ni][g][i];
+                            for (int i = 0; i < 4; ++i) v[i] += bias32[ni][g][i];
+                        }
                     }
                     if (RELU) {
 #pragma unroll
@@ -707,7 +727,19 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             }
             return;
         }
-        constexpr int WAITN = (STAGES - 2) * LPS;
+        constexpr int WAITN = STAGES >= 2 ? (STAGES - 2) * LPS : 0;
+        // s_waitcnt vmcnt(WAITN), through the builtin and not as inline assembly: the compiler's own wait-count
+        // bookkeeping reads the builtin and then knows that every older load has landed.  It cannot see into
+        // inline assembly; with that, a register load left over from an epilogue counted as still in flight
+        // and the compiler drained the whole load pipeline (vmcnt(0)) at the top of every K iteration.
+        // Encoding: vmcnt in bits 3:0 and 15:14, expcnt (bits 6:4) and lgkmcnt (bits 11:8) left at "no wait".
+        auto wait_loads = [&]() {
+            static_assert(WAITN >= 0 && WAITN < 64, "vmcnt is a 6-bit counter");
+            constexpr int kWaitImm = (WAITN & 15) | ((WAITN >> 4) << 14) | (7 << 4) | (15 << 8);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(kWaitImm);
+            asm volatile("" ::: "memory");
+        };
         int l_seq = seq, l_kt = 0, l_stage = 0;
         bool l_more = true;
         set_ptrs(t);
@@ -749,7 +781,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         }
 #pragma unroll
         for (int i = 0; i < STAGES - 1; ++i) issue_next();
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WAITN) : "memory");
+        wait_loads();
         stage_barrier();
         int stage = 0;
         while (true) {
@@ -764,7 +796,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 }
                 issue_next();  // into the stage the previous iteration computed from
                 compute(stage, kt);
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WAITN) : "memory");
+                wait_loads();
                 stage_barrier();
                 stage = (stage + 1 == STAGES) ? 0 : stage + 1;
             }
