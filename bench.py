@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0         # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
-VALU_F32_PEAK_TFLOPS = 157.3  # fp32 vector
+MFMA_F32_PEAK_TFLOPS = 157.3  # dense fp32 MFMA (the fp32 GEMMs run on v_mfma_f32_32x32x2_f32)
 
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
@@ -65,12 +65,12 @@ def kernel_models(w, counts):
 def roofline_entry(name, model, ms, dtype):
     """Which roof bounds the kernel and the achieved fraction of it."""
     secs = ms * 1e-3
-    peak_tf = MFMA_BF16_PEAK_TFLOPS if dtype == "bf16" else VALU_F32_PEAK_TFLOPS
+    peak_tf = MFMA_BF16_PEAK_TFLOPS if dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
     t_mem = model["bytes"] / (HBM_PEAK_GBS * 1e9)
     t_alu = model["flops"] / (peak_tf * 1e12)
     if t_alu > t_mem:
         ach = model["flops"] / secs / 1e12
-        return dict(kernel=name, bound="mfma" if dtype == "bf16" else "alu", achieved=ach, peak=peak_tf,
+        return dict(kernel=name, bound="mfma", achieved=ach, peak=peak_tf,
                     unit="TFLOP/s", frac=ach / peak_tf, traffic=None, avg_ms=ms)
     ach = model["bytes"] / secs / 1e9
     return dict(kernel=name, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
