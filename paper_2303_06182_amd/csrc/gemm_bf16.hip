@@ -65,6 +65,26 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
 
+// One 32-bit word at an address that is the same for every lane of the wave, through the scalar data path
+// (read only).  The compiler issues such loads as vector loads here (it cannot prove that the kernel's own
+// stores leave the tile map alone), and a vector load's result can only be waited for together with every
+// vector load issued before it -- at a tile switch that drains the whole operand pipeline.  The scalar path
+// has its own counter.  The words read were written by an earlier kernel.
+__device__ __forceinline__ int32_t uniform_load(const int32_t *ptr)
+{
+    int32_t v;
+    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(ptr) : "memory");
+    return v;
+}
+// two independent words with one wait
+__device__ __forceinline__ void uniform_load2(const int32_t *pa, const int32_t *pb, int32_t &a, int32_t &b)
+{
+    asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(a), "=&s"(b)
+                 : "s"(pa), "s"(pb)
+                 : "memory");
+}
+
 static constexpr int BK = 64;
 static constexpr int GROUP_M = 4;
 static constexpr int REG_STAGED = 0;  // value of the STAGES template argument that selects the register-staged pipeline
@@ -184,9 +204,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         const int nt = within / gsz;
         TileInfo t;
         if (GROUPED) {
-            t.expert = p.tile_expert[mt];
-            t.row0 = p.tile_row[mt];
-            t.row_end = p.offsets[t.expert + 1];
+            uniform_load2(p.tile_expert + mt, p.tile_row + mt, t.expert, t.row0);
+            t.row_end = uniform_load(p.offsets + t.expert + 1);
         } else {
             t.expert = 0;
             t.row0 = mt * BM;
@@ -511,7 +530,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         int a_off[A_IT], b_off[B_IT];
         auto set_ptrs = [&](const TileInfo &ti) {
             // weights of expert e sit in slot b_slot[e] of the weight array when experts are buffered
-            const uint16_t *Bg = Bg0 + (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
+            const uint16_t *Bg = Bg0 + (int64_t)((GROUPED && p.b_slot) ? uniform_load(p.b_slot + ti.expert) : ti.expert) * p.strideB;
             int gr0 = 0, gn0 = 0;
 #pragma unroll
             for (int i = 0; i < A_IT; ++i) {
@@ -534,7 +553,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 // quantiser's layout), so the offsets are those of the group; they are in bytes,
                 // carried as half as many 16-bit units.
                 const uint8_t *Bg8 = reinterpret_cast<const uint8_t *>(Bg0) +
-                                     (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
+                                     (int64_t)((GROUPED && p.b_slot) ? uniform_load(p.b_slot + ti.expert) : ti.expert) * p.strideB;
                 const int group_bytes = (K / BK) * 1024;  // one 16-row group over the whole of K
                 const int last_group = p.N / 16 - 1;       // groups past the end repeat the last one
 #pragma unroll
@@ -553,7 +572,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 // (L & 1); in memory that 1 KB block is contiguous and the blocks of a 32-row group follow
                 // each other along K (the quantiser's layout)
                 const uint8_t *Bg4 = reinterpret_cast<const uint8_t *>(Bg0) +
-                                     (int64_t)((GROUPED && p.b_slot) ? p.b_slot[ti.expert] : ti.expert) * p.strideB;
+                                     (int64_t)((GROUPED && p.b_slot) ? uniform_load(p.b_slot + ti.expert) : ti.expert) * p.strideB;
                 const int group_bytes = (K / BK) * 1024;
                 const int last_group = p.N / 32 - 1;
 #pragma unroll
@@ -814,7 +833,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         // chunk c = tid + i*THREADS; row = c >> 3, kc = c & 7
         const int kc = tid & 7;
         while (true) {
-            const uint16_t *Bg = Bg0 + (int64_t)((GROUPED && p.b_slot) ? p.b_slot[t.expert] : t.expert) * p.strideB;
+            const uint16_t *Bg = Bg0 + (int64_t)((GROUPED && p.b_slot) ? uniform_load(p.b_slot + t.expert) : t.expert) * p.strideB;
             const uint16_t *a_ptr[A_IT];
             const uint16_t *b_ptr[B_IT];
             int a_lds[A_IT], b_lds[B_IT];
