@@ -71,6 +71,10 @@ GATE_CASES = [
     # name, dtype, T, D, E, k, renorm, zipf, gate_scale
     ("f32_e8", "f32", 300, 64, 8, 2, True, 0.0, 1.0),
     ("f32_e5_k3_sharp", "f32", 130, 40, 5, 3, False, 0.0, 100.0),
+    # K a multiple of 32: the fp32 MFMA kernel; E = 5 / 70 / 12 take its scalar, ragged and 16-byte stores
+    ("f32_mfma_e5", "f32", 130, 64, 5, 3, False, 0.0, 100.0),
+    ("f32_mfma_e70", "f32", 333, 96, 70, 2, True, 0.0, 50.0),
+    ("f32_mfma_e12_long", "f32", 65, 1024, 12, 2, True, 0.0, 30.0),
     ("bf16_e64_zipf", "bf16", 1000, 256, 64, 2, True, 0.8, 1.0),
     ("bf16_e128_sharp", "bf16", 777, 512, 128, 2, True, 1.2, 100.0),
     ("bf16_e200_k4", "bf16", 200, 128, 200, 4, False, 0.0, 50.0),
@@ -190,6 +194,11 @@ FFN_CASES = [
     ("bf16", [64] * 16, 512, 1024, False),
     ("f32", [100, 0, 37, 64, 1], 64, 128, True),
     ("f32", [300], 128, 256, False),
+    # fp32: D a multiple of 32 but F not (first GEMM on the MFMA kernel, second on the vector-FMA kernel),
+    # and the other way round; many K tiles, several M tiles per expert with ragged ends
+    ("f32", [65, 0, 130, 1], 96, 72, True),
+    ("f32", [65, 0, 130, 1], 72, 96, True),
+    ("f32", [200, 63, 64, 0, 129], 1024, 160, False),
     # 256-row tiles: 24 M tiles x 13 N tiles = 312 tiles on 256 CUs -> one whole round in the main
     # launch, 56 leftover tiles as 128x128 sub-tiles in the tail launch; the second GEMM (24 tiles)
     # runs in the tail launch alone
