@@ -61,6 +61,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 // the explicit vmcnt before each stage barrier is what orders them.
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef uint32_t __attribute__((may_alias)) u32_lds;
+typedef uint16_t __attribute__((may_alias)) u16_lds;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) void glb_void;
@@ -241,13 +242,26 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     const int swz = (lane >> 1) & 7;  // == (row >> 1) & 7 for every row this lane reads
 
     // MFMAs of one K tile out of LDS stage `cur`.
-    // 4-bit weights: the scale bytes of this lane's NI weight rows for 8 consecutive K tiles (16 bytes:
-    // two 32-element blocks per K tile), for the K tiles being computed and for the 8 after them
-    uint4 sc_cur[B4 ? NI : 1], sc_nxt[B4 ? NI : 1];
+    // 4-bit weights: the block scales are staged in LDS too, behind the operand stages: two buffers of
+    // 16 bytes per weight row of the tile (the scales of 8 consecutive K tiles, two 32-element blocks per K
+    // tile), one for the 8 K tiles being computed (c_buf) and one being filled for the 8 after them.
+    // (Kept in registers instead, the refill every 8th K tile made the compiler wait for the load it had
+    // just issued -- a full memory latency with the whole operand pipeline drained.)
+    uint8_t *sS = reinterpret_cast<uint8_t *>(sB + NSTAGE * BTILE);
+    static_assert(!B4 || BN * 16 == (THREADS / 64) * 1024, "one 1 KB scale load per wave covers the tile's rows");
+    int c_buf = 0;
     auto compute = [&](int cur, int kt) {
         const uint16_t *cA = sA + cur * BM * BK + (wm * WTM + frag_row) * BK;
         const uint16_t *cB = sB + cur * BTILE + (wn * WTN + frag_row) * BROW;
         (void)kt;
+        uint32_t sc2[B4 ? NI : 1];
+        if constexpr (B4) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                sc2[ni] = *reinterpret_cast<const u16_lds *>(sS + c_buf * (BN * 16) + (wn * WTN + ni * 32 + frag_row) * 16 +
+                                                             ((kt & 7) << 1));
+        }
+        (void)sc2;
         bf16x8 af[2][MI], bfr[2][NI];
         auto load_frags = [&](int ks, int set) {
             const int chunkpos = ((ks * 2 + frag_half) ^ swz) << 3;
@@ -272,17 +286,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 }
             } else if constexpr (B4) {
                 // 32-byte rows; this lane's 8 elements of K-step ks are the 4 bytes at ks*8 + half*4, their
-                // block scale is byte (kt mod 8)*2 + ks/2 of the row's 16 scale bytes
-                const int sb = ((kt & 7) << 1) + (ks >> 1);
+                // block scale is byte (kt mod 8)*2 + ks/2 of the row's 16 scale bytes (sc2: the K tile's two)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const uint32_t raw = *reinterpret_cast<const u32_lds *>(reinterpret_cast<const uint8_t *>(cB) +
                                                                             ni * 32 * (BK / 2) + ks * 8 + frag_half * 4);
-                    const uint32_t w4[4] = {sc_cur[ni].x, sc_cur[ni].y, sc_cur[ni].z, sc_cur[ni].w};
-                    uint32_t word = w4[0];
-#pragma unroll
-                    for (int q = 1; q < 4; ++q) word = (sb >> 2) == q ? w4[q] : word;
-                    const float scale = __uint_as_float(((word >> ((sb & 3) << 3)) & 0xffu) << 23);  // 2^(byte - 127)
+                    const float scale = __uint_as_float(((sc2[ni] >> ((ks >> 1) << 3)) & 0xffu) << 23);  // 2^(byte - 127)
                     const bf16x2 d0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 0);
                     const bf16x2 d1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 1);
                     const bf16x2 d2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(raw, scale, 2);
@@ -776,27 +785,37 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 }
             }
         };
-        // 4-bit weights: the scale bytes run one group of 8 K tiles ahead of the MFMAs, across tile borders
-        int s_seq = seq, s_grp = 0;
-        auto load_scales = [&](uint4(&dst)[B4 ? NI : 1]) {
+        // 4-bit weights: the scale bytes run one group of 8 K tiles ahead of the MFMAs, across tile borders.
+        // One load instruction per wave fills 64 rows x 16 bytes of the buffer: lane L fetches the 16 bytes
+        // of row 64 * wave + L (row group 2 * wave + L / 32 of the tile, row L % 32 of that group's 512-byte
+        // block).  These loads are older than the operand loads issued after them, and loads complete in
+        // order, so the per-iteration vmcnt wait covers them once two iterations have passed.
+        int s_seq = seq, s_grp = 0, s_buf = 0;
+        const uint8_t *s_lane = nullptr;
+        const int s_groups = (KT + 7) >> 3;  // 16-byte scale groups per weight row
+        auto scale_tile = [&]() {
+            const TileInfo ts = tile_info(s_seq);
+            const int rg = min((ts.n0 + wave * 64 + (lane >> 5) * 32) >> 5, p.N / 32 - 1);
+            s_lane = p.b_blk_scale + (int64_t)ts.expert * p.stride_blk_scale + (int64_t)rg * s_groups * 512 + (lane & 31) * 16;
+        };
+        auto issue_scales = [&]() {
             if constexpr (B4) {
-                const TileInfo ts = tile_info(s_seq);
-                const int groups = (KT + 7) >> 3;  // 16-byte scale groups per weight row
-                const uint8_t *sb = p.b_blk_scale + (int64_t)ts.expert * p.stride_blk_scale;
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int ng = min((ts.n0 + wn * WTN + ni * 32) >> 5, p.N / 32 - 1);
-                    dst[ni] = *reinterpret_cast<const uint4 *>(sb + ((int64_t)ng * groups + s_grp) * 512 + frag_row * 16);
-                }
-                if (++s_grp == groups) {  // on to the next tile of this block, if there is one
+                __builtin_amdgcn_global_load_lds((const glb_void *)(s_lane + s_grp * 512),
+                                                 (lds_void *)(sS + s_buf * (BN * 16) + wave * 1024), 16, 0, 0);
+                s_buf ^= 1;
+                if (++s_grp == s_groups) {  // on to the next tile of this block, if there is one
                     s_grp = 0;
-                    if (seq_ok(s_seq + slots)) s_seq += slots;
+                    if (seq_ok(s_seq + slots)) {
+                        s_seq += slots;
+                        scale_tile();
+                    }
                 }
             }
         };
         if constexpr (B4) {
-            load_scales(sc_cur);
-            load_scales(sc_nxt);
+            scale_tile();
+            issue_scales();
+            issue_scales();
         }
 #pragma unroll
         for (int i = 0; i < STAGES - 1; ++i) issue_next();
@@ -808,9 +827,14 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             for (int kt = 0; kt < KT; ++kt) {
                 if constexpr (B4) {
                     if ((kt & 7) == 0 && (kt > 0 || seq != (int)(blockIdx.x >> 3))) {  // a new group of 8 K tiles
-#pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) sc_cur[ni] = sc_nxt[ni];
-                        load_scales(sc_nxt);
+                        if (KT < STAGES) {
+                            // groups shorter than the pipeline is deep: the scales requested one group ago
+                            // may not have landed yet
+                            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                            stage_barrier();
+                        }
+                        c_buf ^= 1;
+                        issue_scales();  // into the buffer of the group just finished
                     }
                 }
                 issue_next();  // into the stage the previous iteration computed from
@@ -895,7 +919,8 @@ static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *mai
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (BQ == 8 ? BN / 2 : BQ == 4 ? BN / 4 : BN)) * BK * sizeof(uint16_t);
+    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (BQ == 8 ? BN / 2 : BQ == 4 ? BN / 4 : BN)) * BK * sizeof(uint16_t) +
+                        (BQ == 4 ? 2 * BN * 16 : 0);  // 4-bit weights: two buffers of block scales
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES, BQ>;
     static int blocks_per_cu = 0;  // per instantiation
     if (blocks_per_cu == 0) {
@@ -1000,9 +1025,11 @@ int gemm_bf16_variant_w8(int64_t n_rows, int E)
     return avg >= 48 ? 22 : 23;
 }
 
-// 4-bit weights: 43 = 32x256, 48 = 64x256, four LDS stages each.  (Measured on 128 experts of 2048 x 8192
+// 4-bit weights: 43 = 32x256, 48 = 64x256, three LDS stages each plus the two scale buffers (32x256: 44 KB,
+// three blocks per CU; a fourth stage would leave room for two, 0.141 -> 0.154 ms on the decoder's first
+// GEMM; two stages 0.150).  (Measured on 128 experts of 2048 x 8192
 // with 1 to 64 rows each: 256 columns per tile beat 128 by 25-30 % -- the A tile, re-read once per column
-// tile, weighs as much as a 128-column B tile at 4 bits -- and 512 lost again; 3, 4 and 6 stages +-5 %.
+// tile, weighs as much as a 128-column B tile at 4 bits -- and 512 lost again.
 // With 8 or 16 tokens the second GEMM has fewer tiles than CUs and its time is the K loop of one tile,
 // 128 K tiles at about 0.65 us each, whatever the tile width or pipeline depth: only a split along K
 // would shorten it.)
@@ -1110,8 +1137,8 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
     case 1: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
     case 22: return launch_grouped_w8<64, 128, 1, 4, 2, 3>(p, relu, num_cus, s);
     case 23: return launch_grouped_w8<32, 128, 1, 4, 2, 4>(p, relu, num_cus, s);
-    case 43: return launch_grouped_w8<32, 256, 1, 4, 2, 4, 4>(p, relu, num_cus, s);
-    case 48: return launch_grouped_w8<64, 256, 1, 4, 2, 4, 4>(p, relu, num_cus, s);
+    case 43: return launch_grouped_w8<32, 256, 1, 4, 2, 3, 4>(p, relu, num_cus, s);
+    case 48: return launch_grouped_w8<64, 256, 1, 4, 2, 3, 4>(p, relu, num_cus, s);
     case 2: return launch_grouped<64, 128, 1, 4, 2>(p, relu, num_cus, s);
     case 3: return launch_grouped<32, 128, 1, 4, 2>(p, relu, num_cus, s);
     default:

@@ -79,6 +79,9 @@ W4_FFN_CASES = [
     ([64, 48, 100, 47, 70, 90], 192, 320, False),   # 64-row tiles; N = 320 / 192 not multiples of the tile width
     ([700, 45], 64, 64, True),
     ([3, 2, 0, 1], 1088, 576, False),               # K = 1088 = 17 K tiles: three scale groups, the last one short
+    # 1000 tiles of one or two K tiles each on ~768 resident blocks: blocks run two tiles, and a scale group is
+    # shorter than the load pipeline is deep
+    ([2] * 1000, 64, 128, False),
 ]
 
 
