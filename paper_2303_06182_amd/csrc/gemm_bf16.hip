@@ -346,7 +346,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         }
         const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
         if (bias) bias += (int64_t)t.expert * p.strideBias;
-        const float b_scale = (B8 && p.b_scale) ? p.b_scale[t.expert] : 1.f;
+        const float b_scale = (B8 && p.b_scale) ? __int_as_float(uniform_load(reinterpret_cast<const int32_t *>(p.b_scale) + t.expert)) : 1.f;
         (void)b_scale;
         const bool vec_ok = !OUT_F32 || ((p.ldc & 3) == 0 && (p.N & 3) == 0);
         // The fp32 offsets of this lane's columns are fetched before the first store: a load
@@ -464,7 +464,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                                              : sB + free_stage * BTILE + wave * B_IT * 8 * BK);
         const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
         if (bias) bias += (int64_t)t.expert * p.strideBias;
-        const float b_scale = (B8 && p.b_scale) ? p.b_scale[t.expert] : 1.f;
+        const float b_scale = (B8 && p.b_scale) ? __int_as_float(uniform_load(reinterpret_cast<const int32_t *>(p.b_scale) + t.expert)) : 1.f;
         (void)b_scale;
         const int r = lane & 31;
         const int col_base = t.n0 + wn * WTN;
