@@ -382,7 +382,7 @@ def yardsticks():
     out["copy_GBps"] = 20 * 2 * (1 << 30) / (time.perf_counter() - t0) / 1e9
     del src, dst
     gemms = {}
-    for label, (M, K, N) in (("32768x2048x8192", (32768, 2048, 8192)), ("32768x8192x2048", (32768, 8192, 2048))):
+    for label, (M, K, N) in (("M32768_K2048_N8192", (32768, 2048, 8192)), ("M32768_K8192_N2048", (32768, 8192, 2048))):
         a = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
         b = torch.randn(N, K, device="cuda", dtype=torch.bfloat16)
         for _ in range(3):
