@@ -184,6 +184,23 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
                       int32_t T, void *y, const moe_routing_t *routing_out,
                       void *workspace, int64_t workspace_bytes, void *stream);
 
+/* moe_layer_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops (one decode step after the other), harnesses that
+ * forbid hipMalloc.  Same arguments minus the workspace, same kernels, same result bit for bit.  The
+ * scratch is an array of MOE_NOALLOC_SCRATCH_BYTES bytes that lives inside the library, once per GPU
+ * the library runs on, until the process ends; the call allocates nothing (no hipMalloc / hipFree,
+ * no allocating library routine) and still only enqueues work on `stream`.
+ *   - The handle's moe_workspace_bytes() must fit: MOE_ERR_WORKSPACE otherwise (a handle made for
+ *     decode-sized batches does: T_max = 64, D = 2048, F = 8192, E = 128, k = 2 needs 3.6 MB).
+ *   - The current device must be the one the handle was created on (MOE_ERR_INVALID_ARG otherwise).
+ *   - Every such call on one GPU uses the same array: calls that may overlap in time on one GPU
+ *     (different streams, different threads, different handles) race.  The array keeps the previous
+ *     call's contents; nothing in it has to be cleared between calls. */
+#define MOE_NOALLOC_SCRATCH_BYTES (8 * 1024 * 1024)
+int moe_layer_forward_noalloc(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias,
+                              const void *w1, const void *w2, const void *b1, const void *b2,
+                              int32_t T, void *y, const moe_routing_t *routing_out, void *stream);
+
 /* Static-capacity baseline (Sec. 3.2, Sec. 5.1): same gate; every expert owns
  * `capacity` rows; assignments are placed slot by slot (all first choices in token
  * order, then all second choices, ...) into the first empty row of their expert and

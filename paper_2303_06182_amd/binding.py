@@ -37,8 +37,9 @@ EXPORTS = [
     "moe_placement_greedy", "moe_placement_anticorrelation", "moe_placement_loads",
     "moe_quantize_e4m3", "moe_expert_ffn_w8", "moe_layer_forward_w8",
     "moe_mxfp4_scale_bytes", "moe_quantize_mxfp4", "moe_expert_ffn_w4", "moe_layer_forward_w4",
-    "moe_expert_cache_bytes_q", "moe_expert_cache_create_q",
+    "moe_expert_cache_bytes_q", "moe_expert_cache_create_q", "moe_layer_forward_noalloc",
 ]
+MOE_NOALLOC_SCRATCH_BYTES = 8 * 1024 * 1024
 
 
 class MoeConfig(ctypes.Structure):
@@ -95,6 +96,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_combine.restype = ctypes.c_int
     lib.moe_layer_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting), vp, i64, vp]
     lib.moe_layer_forward.restype = ctypes.c_int
+    lib.moe_layer_forward_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.POINTER(MoeRouting), vp]
+    lib.moe_layer_forward_noalloc.restype = ctypes.c_int
     lib.moe_layer_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp,
                                              ctypes.POINTER(MoeRouting), vp, i64, vp]
     lib.moe_layer_forward_static.restype = ctypes.c_int
@@ -292,6 +295,14 @@ class MoeLayer:
         _check(self.lib.moe_layer_forward(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1), _ptr(w2), _ptr(b1),
                                           _ptr(b2), T, _ptr(y), self._routing_struct(routing_out), ws, wsb,
                                           _stream()))
+        return y
+
+    def moe_layer_forward_noalloc(self, x, wg, w1, w2, y, gate_bias=None, b1=None, b2=None, routing_out=None):
+        """moe_layer_forward on the library's own scratch array: no workspace, and nothing is allocated
+        here either (the caller brings y and the routing arrays)."""
+        _check(self.lib.moe_layer_forward_noalloc(self.h, _ptr(x), _ptr(wg), _ptr(gate_bias), _ptr(w1), _ptr(w2),
+                                                  _ptr(b1), _ptr(b2), x.shape[0], _ptr(y),
+                                                  self._routing_struct(routing_out), _stream()))
         return y
 
     def moe_quantize_e4m3(self, w):

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -27,6 +28,40 @@ int hip_failed(hipError_t e, const char *what)
 {
     set_error("HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
     return MOE_ERR_HIP;
+}
+
+// ---- scratch for the entry point that allocates nothing -------------------------------------------
+// moe_layer_forward_noalloc carves its workspace out of this array instead of a caller buffer.  Every
+// device the library runs on holds its own copy at its own address until the process ends.  On the
+// host the array's name is only a handle for hipGetSymbolAddress: the address that kernels, copies
+// and fills get is the one that call returned for the current device (scratch_for_device), never
+// the name.
+static __device__ __align__(256) __attribute__((used)) uint8_t scratch[MOE_NOALLOC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];  // per device ordinal; NULL = not looked up yet
+
+// Address of `scratch` on device `dev`, which must be the current device.  Looked up once per device.
+static int scratch_for_device(int dev, void **out)
+{
+    *out = nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("device ordinal %d outside [0, %d)", dev, kMaxDevices);
+        return MOE_ERR_INVALID_ARG;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        MOE_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256 != 0) {
+            set_error("the library's scratch array has no usable device address");
+            return MOE_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
 }
 
 // ---- per-kernel event timing ---------------------------------------------------------------------
@@ -505,6 +540,12 @@ int moe_create(const moe_config_t *cfg, moe_handle_t **out)
     h->cfg = *cfg;
     h->device = dev;
     h->num_cus = prop.multiProcessorCount;
+    // the current device is `dev`: the one moment at which its copy of the scratch array can be looked up
+    rc = scratch_for_device(dev, &h->scratch);
+    if (rc != MOE_OK) {
+        delete h;
+        return rc;
+    }
     *out = h;
     return MOE_OK;
 }
@@ -770,6 +811,35 @@ int moe_layer_forward(moe_handle_t *h, const void *x, const void *wg, const floa
 {
     return layer_forward_impl(h, nullptr, x, wg, gate_bias, w1, w2, b1, b2, T, y, routing_out, workspace,
                               workspace_bytes, stream);
+}
+
+// moe_layer_forward for callers that cannot allocate: the workspace is the library's own scratch
+// array on the handle's device.  No allocation of any kind happens here or below.
+int moe_layer_forward_noalloc(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, const void *w1,
+                              const void *w2, const void *b1, const void *b2, int32_t T, void *y,
+                              const moe_routing_t *routing_out, void *stream)
+{
+    g_err[0] = 0;
+    if (!h) {
+        set_error("handle is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    const int64_t need = ws_layout(h->cfg).total;
+    if (need > (int64_t)MOE_NOALLOC_SCRATCH_BYTES) {
+        set_error("moe_layer_forward_noalloc: this handle (T_max = %d) needs %lld bytes of scratch, the library holds %lld; "
+                  "use moe_layer_forward with a workspace of the caller's", h->cfg.T_max, (long long)need,
+                  (long long)MOE_NOALLOC_SCRATCH_BYTES);
+        return MOE_ERR_WORKSPACE;
+    }
+    int dev = -1;
+    MOE_HIP_CHECK(hipGetDevice(&dev));
+    if (dev != h->device || !h->scratch) {
+        set_error("moe_layer_forward_noalloc: current device %d is not the handle's device %d", dev, h->device);
+        return MOE_ERR_INVALID_ARG;
+    }
+    // nothing in the workspace has to start at zero: every slice is written by the call before it is read
+    return layer_forward_impl(h, nullptr, x, wg, gate_bias, w1, w2, b1, b2, T, y, routing_out, h->scratch,
+                              (int64_t)MOE_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 // ---- 8-bit expert weights -----------------------------------------------------------------------

@@ -49,6 +49,7 @@ struct moe_handle {
     moe_config_t cfg;
     int device;
     int num_cus;
+    void *scratch;  // device address of the library's own scratch array on `device` (moe_layer_forward_noalloc)
     moe355::Profiler prof;
 };
 
