@@ -8,7 +8,10 @@ tokens/s of the whole layer, the roofline figures of the dominant kernel (live H
 timing on the stream the kernels run on), a per-kernel breakdown, and the CPU oracle timed
 on the host cores as a reported baseline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config lm] [--also skewed_large]
+The headline workload is `skewed_large`, the largest of the five (T 65536, E 128, 2048 -> 8192, Zipf 1.2);
+the other four are reported under "also".
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config skewed_large] [--also lm,...]
 """
 from __future__ import annotations
 
@@ -27,22 +30,68 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 MFMA_F32_PEAK_TFLOPS = 157.3  # dense fp32 MFMA (the fp32 GEMMs run on v_mfma_f32_32x32x2_f32)
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
-# 1 GiB calibration kernel: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE; see profiles/moe_layer_forward_*.txt; an
-# expert GEMM's figure is the sum over its two launches).
-# Counter runs cannot be made from inside this script, so the figures of the committed profiles are
-# quoted for the kernels they cover; any other (workload, kernel) reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("lm", "expert_gemm1"): 819970 * 1024, ("lm", "expert_gemm2"): 834941 * 1024,
-    ("lm", "dispatch"): 49381 * 1024, ("lm", "combine"): 49531 * 1024, ("lm", "gate_gemm"): 19595 * 1024,
-    ("skewed_large", "expert_gemm1"): 13435094 * 1024, ("skewed_large", "expert_gemm2"): 10874901 * 1024,
-    ("skewed_large", "dispatch"): 788772 * 1024, ("skewed_large", "combine"): 790912 * 1024,
-    ("skewed_large", "gate_gemm"): 299262 * 1024,
-    ("mt_encoder", "expert_gemm1"): 2716482 * 1024, ("mt_encoder", "expert_gemm2"): 2318591 * 1024,
-    ("mt_encoder", "dispatch"): 197257 * 1024, ("mt_encoder", "combine"): 197871 * 1024,
-    ("mt_encoder", "gate_gemm"): 67212 * 1024,
-    ("mt_decoder", "expert_gemm1"): (2 * 1328785 + 2048) * 1024, ("mt_decoder", "expert_gemm2"): (2 * 1330728 + 512) * 1024,
-}
+# Every timed block is preceded by a fixed, untimed pre-conditioning phase of this many seconds of the same
+# steps (on top of --warmup): the device's clocks and power state settle over a few hundred milliseconds of
+# load, and a short warm-up otherwise leaves the first timed steps slow (20 steps after 5 warm-up steps read
+# up to 17 % slower than 200 after 50).
+PRECONDITION_SECONDS = 1.0
+
+# Last-level cache of the device (the 256 MB cache in front of HBM): a workload whose weights fit keeps them
+# there between steps, so such a workload is also run "cold", rotating through enough copies of its weights.
+LAST_LEVEL_CACHE_BYTES = 256 << 20
+
+
+def profile_kernel_name(kernel: str):
+    """bench name of a kernel row of profiles/moe_layer_forward_*.txt (None = not one of the layer's steps)."""
+    k = kernel.strip()
+    if k.startswith("gemm_bf16_kernel<") or k.startswith("gemm_f32"):
+        args = [a.strip() for a in k[k.index("<") + 1:].rstrip(">").split(",")]
+        if k.startswith("gemm_bf16_kernel<"):
+            out_f32, relu, grouped = args[4] == "true", args[5] == "true", args[6] == "true"
+            if len(args) > 10 and args[10] != "0":
+                return None  # quantised weights (the weight_formats runs), not the bf16 layer
+        else:  # gemm_f32_*<RELU, GROUPED, ...>
+            out_f32, relu, grouped = False, args[0] == "true", args[1] == "true"
+        if not grouped:
+            return "gate_gemm" if (out_f32 or k.startswith("gemm_f32")) else None
+        return "expert_gemm1" if relu else "expert_gemm2"
+    for prefix, name in (("gate_topk_kernel", "gate_gemm"), ("topk_kernel", "topk"), ("route_", "route"),
+                         ("dispatch_kernel", "dispatch"), ("combine_kernel", "combine"), ("tile_map_kernel", "tile_map")):
+        if k.startswith(prefix):
+            return name
+    return None
+
+
+def traffic_from_profile(workload: str, profiles_dir: str = None):
+    """HBM-side bytes per launch of every kernel of the layer, from the committed rocprofv3 counter summary
+    profiles/moe_layer_forward_<workload>.txt: the FETCH_SIZE and WRITE_SIZE sections (KiB per dispatch, two
+    --pmc runs), each scaled by what the same counter reads for the 1 GiB-read + 1 GiB-write calibration kernel
+    of the same run (the row of torch's elementwise add).  A step made of several launches (an expert GEMM's main and
+    tail launch, the routing kernels) is the sum over them.  {} when there is no summary for the workload."""
+    path = os.path.join(profiles_dir or os.path.join(ROOT, "profiles"), "moe_layer_forward_%s.txt" % workload)
+    if not os.path.exists(path):
+        return {}
+    section, rows = None, {"FETCH_SIZE": {}, "WRITE_SIZE": {}}
+    for line in open(path):
+        if line.startswith("== "):
+            section = line[3:].split()[0]
+            continue
+        if section in rows and " KiB" in line and " n=" in line:
+            kernel = line[:line.index(" n=")].strip()
+            rows[section][kernel] = rows[section].get(kernel, 0.0) + float(line.rsplit("KiB", 1)[0].split()[-1])
+    out = {}
+    factors = {}
+    for sec in rows:
+        calib = [v for k, v in rows[sec].items() if "FunctorOnSelf_add<int>" in k]
+        if not calib:
+            return {}
+        factors[sec] = (1 << 20) / calib[0]   # the calibration kernel moves 1 GiB = 2^20 KiB each way
+    for sec in rows:
+        for kernel, kib in rows[sec].items():
+            name = profile_kernel_name(kernel)
+            if name:
+                out[name] = out.get(name, 0.0) + factors[sec] * kib * 1024.0
+    return {k: int(round(v)) for k, v in out.items()}
 
 
 def kernel_models(w, counts):
@@ -79,24 +128,23 @@ def roofline_entry(name, model, ms, dtype):
                 traffic=None, avg_ms=ms)
 
 
-def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
-    import numpy as np
+def precondition(step, seconds=PRECONDITION_SECONDS):
+    """Untimed steps for a fixed wall time, so that every timed block starts from the same clock / power state
+    whatever --warmup says."""
     import torch
-    from paper_2303_06182_amd import binding, workloads as wl
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(4):
+            step()
+        torch.cuda.synchronize()
+        n += 4
+    return n
 
-    w = wl.CONFIGS[name]
-    inp = wl.make_inputs(w, device="cuda")
-    host = {k: (None if v is None else v.cpu()) for k, v in inp.items()} if keep_host_copy else None
-    layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
-    y = torch.empty((w.T, w.D), dtype=w.torch_dtype, device="cuda")
-    routing = layer.empty_routing(w.T)
 
-    def step():
-        layer.moe_layer_forward(inp["x"], inp["wg"], inp["w1"], inp["w2"], inp["gate_bias"], y=y,
-                                routing_out=routing)
-
-    for _ in range(warmup):
-        step()
+def timed_block(step, steps):
+    """EXACTLY `steps` steps between synchronisations; the larger of wall clock and stream events."""
+    import torch
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
@@ -106,8 +154,28 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    ev_ms = ev0.elapsed_time(ev1)
-    ms_per_step = max(wall_ms, ev_ms) / steps
+    return max(wall_ms, ev0.elapsed_time(ev1)) / steps
+
+
+def run_config(name, steps, warmup, profile_steps=10, cold_copies=0):
+    import numpy as np
+    import torch
+    from paper_2303_06182_amd import binding, workloads as wl
+
+    w = wl.CONFIGS[name]
+    inp = wl.make_inputs(w, device="cuda")
+    layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
+    y = torch.empty((w.T, w.D), dtype=w.torch_dtype, device="cuda")
+    routing = layer.empty_routing(w.T)
+
+    def step():
+        layer.moe_layer_forward(inp["x"], inp["wg"], inp["w1"], inp["w2"], inp["gate_bias"], y=y,
+                                routing_out=routing)
+
+    pre_steps = precondition(step)
+    for _ in range(warmup):
+        step()
+    ms_per_step = timed_block(step, steps)
     counts = routing["counts"].cpu().numpy()
 
     # the spread behind the mean: the same steps again, each between an event pair of its own
@@ -122,7 +190,27 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
     # bytes one step must touch (expert weights with rows + activations): against the 256 MB last-level
     # cache this says whether a step can find its weights cached from the step before
     es = 2 if w.dtype == "bf16" else 4
-    working_set = int((counts > 0).sum()) * 2 * w.D * w.F * es + w.T * w.k * (2 * w.D + w.F) * es
+    weight_bytes = int((counts > 0).sum()) * 2 * w.D * w.F * es
+    working_set = weight_bytes + w.T * w.k * (2 * w.D + w.F) * es
+
+    # a workload whose weights fit the last-level cache: the same steps again, every step on the next of
+    # `cold_copies` copies of the weights, so that no step finds its weights cached
+    cold = None
+    if cold_copies > 1:
+        copies = [(inp["w1"], inp["w2"], inp["wg"])] + [(inp["w1"].clone(), inp["w2"].clone(), inp["wg"].clone())
+                                                       for _ in range(cold_copies - 1)]
+        turn = [0]
+
+        def cold_step():
+            w1, w2, wg = copies[turn[0] % len(copies)]
+            turn[0] += 1
+            layer.moe_layer_forward(inp["x"], wg, w1, w2, inp["gate_bias"], y=y, routing_out=routing)
+
+        precondition(cold_step)
+        cold = dict(ms_per_step=timed_block(cold_step, steps), weight_copies=cold_copies,
+                    rotated_bytes=cold_copies * weight_bytes)
+        cold["tokens_per_s"] = w.T / (cold["ms_per_step"] * 1e-3)
+        del copies
 
     # per-kernel durations: HIP events recorded by the library around every launch, on the same stream
     acc = {}
@@ -142,12 +230,18 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
                 acc.setdefault(kname, []).append(ms)
         del xp
         standalone.add("dispatch")
+    # what an event pair around nothing reads: subtracted from every record (it is a third to a half of what
+    # the events show for the kernels of 5 to 20 us)
+    overhead_ms = float(np.median(acc.pop("event_pair_overhead", [0.0])))
     kernels = {}
     models = kernel_models(w, counts)
+    traffic = traffic_from_profile(name)
     for kname, v in acc.items():
-        ms = float(np.mean(v))
+        raw = float(np.mean(v))
+        ms = max(raw - overhead_ms, 0.25 * raw)
         kernels[kname] = roofline_entry(kname, models[kname], ms, w.dtype)
-        kernels[kname]["traffic"] = MEASURED_TRAFFIC_BYTES.get((name, kname))
+        kernels[kname]["event_ms"] = raw
+        kernels[kname]["traffic"] = traffic.get(kname)
         kernels[kname]["algorithmic_bytes"] = models[kname]["bytes"]
         kernels[kname]["algorithmic_flops"] = models[kname]["flops"]
         if kname in standalone:
@@ -155,18 +249,21 @@ def run_config(name, steps, warmup, profile_steps=10, keep_host_copy=False):
     dominant = max((r for r in kernels.values() if r.get("in_fused_call", True)), key=lambda r: r["avg_ms"])
     res = dict(workload=name, T=w.T, D=w.D, F=w.F, E=w.E, k=w.k, dtype=w.dtype,
                ms_per_step=ms_per_step, tokens_per_s=w.T / (ms_per_step * 1e-3), step_ms=step_ms,
-               working_set_bytes=working_set,
+               working_set_bytes=working_set, precondition_steps=pre_steps, event_pair_overhead_ms=overhead_ms,
                max_expert_share=float(counts.max() / counts.sum()), idle_experts=int((counts == 0).sum()),
-               workspace_bytes=layer.workspace_bytes, dominant=dominant, kernels=kernels, host=host)
+               max_expert_rows=int(counts.max()), cold=cold,
+               workspace_bytes=layer.workspace_bytes, dominant=dominant, kernels=kernels)
     del layer, inp, y, routing
     torch.cuda.empty_cache()
     return res
 
 
-def run_static(name, cfs, steps=3):
+def run_static(name, cfs, steps=3, no_drop_rows=0):
     """The static-capacity baseline on the same workload: every expert owns cf * k*T/E rows,
     overflow is dropped, unused rows are zero and still computed.  Both the index-moved and the
-    one-hot-mask ("einsum") forms."""
+    one-hot-mask ("einsum") forms.  no_drop_rows > 0 adds the index-moved form at that capacity -- the
+    busiest expert's row count, i.e. the smallest capacity that drops nothing, which is where the paper's
+    waste factor (rows computed / rows needed, Sec. 3.2) shows without the drops hiding it."""
     import torch
     from paper_2303_06182_amd import binding, workloads as wl
 
@@ -175,31 +272,37 @@ def run_static(name, cfs, steps=3):
     layer = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
     y = torch.empty((w.T, w.D), dtype=w.torch_dtype, device="cuda")
     out = {}
+    runs = []
     for cf in cfs:
         cap = binding.moe_capacity(w.T, w.E, w.k, cf, binding.MOE_CAPACITY_SHARE)
-        for mode, mname in ((binding.MOE_STATIC_INDEXED, "indexed"), (binding.MOE_STATIC_EINSUM, "einsum")):
-            nbytes = layer.moe_static_workspace_bytes(w.T, cap, mode)
-            free, _ = torch.cuda.mem_get_info()
-            if nbytes > free - (8 << 30):
-                out["cf%.1f_%s" % (cf, mname)] = dict(skipped="workspace of %d bytes does not fit" % nbytes)
-                continue
-            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        runs.append(("cf%.1f_indexed" % cf, cap, binding.MOE_STATIC_INDEXED))
+        runs.append(("cf%.1f_einsum" % cf, cap, binding.MOE_STATIC_EINSUM))
+    if no_drop_rows > 0:
+        runs.append(("no_drop_indexed", int(no_drop_rows), binding.MOE_STATIC_INDEXED))
+    for label, cap, mode in runs:
+        nbytes = layer.moe_static_workspace_bytes(w.T, cap, mode)
+        free, _ = torch.cuda.mem_get_info()
+        if nbytes > free - (8 << 30):
+            out[label] = dict(capacity_rows=cap, skipped="workspace of %d bytes does not fit" % nbytes)
+            continue
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
 
-            def step():
-                return layer.moe_layer_forward_static(inp["x"], inp["wg"], inp["w1"], inp["w2"], cap, mode,
-                                                      inp["gate_bias"], y=y, workspace=ws)
-            _, dropped = step()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(steps):
-                step()
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3 / steps
-            out["cf%.1f_%s" % (cf, mname)] = dict(
-                capacity_rows=cap, padded_rows=cap * w.E, needed_rows=w.k * w.T, dropped_assignments=int(dropped[0]),
-                ms_per_step=ms, tokens_per_s=w.T / (ms * 1e-3), workspace_bytes=nbytes)
-            del ws
-            torch.cuda.empty_cache()
+        def step():
+            return layer.moe_layer_forward_static(inp["x"], inp["wg"], inp["w1"], inp["w2"], cap, mode,
+                                                  inp["gate_bias"], y=y, workspace=ws)
+        _, dropped = step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        out[label] = dict(
+            capacity_rows=cap, padded_rows=cap * w.E, needed_rows=w.k * w.T, waste_factor=cap * w.E / (w.k * w.T),
+            dropped_assignments=int(dropped[0]), ms_per_step=ms, tokens_per_s=w.T / (ms * 1e-3),
+            workspace_bytes=nbytes)
+        del ws
+        torch.cuda.empty_cache()
     del layer, inp, y
     torch.cuda.empty_cache()
     return out
@@ -210,11 +313,9 @@ def run_buffering(name, slots_list, n_steps, rho=0.9, tokens=(64, 16)):
     pinned host memory, `slots` experts fit on the device, a synthetic sequence of decode steps with
     temporally correlated expert activity runs through moe_layer_forward_buffered.  Reports the
     throughput, the cache's miss rate and the copied bytes per cache size, beside the plain call
-    (all experts resident) and beside what the oracle's simulator gives for the paper's policy,
-    FIFO, LRU and Belady's MIN on the same activity trace."""
-    import numpy as np
+    (all experts resident).  The observed activity trace is kept for the CPU-baseline leg, which
+    simulates the paper's policy, FIFO, LRU and Belady's MIN on it (cpu_cache_policies)."""
     import torch
-    from oracle import expert_cache as ec
     from paper_2303_06182_amd import binding, workloads as wl
 
     base = wl.CONFIGS[name]
@@ -243,7 +344,6 @@ def run_buffering(name, slots_list, n_steps, rho=0.9, tokens=(64, 16)):
 def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho, fmt=None):
     import numpy as np
     import torch
-    from oracle import expert_cache as ec
     from paper_2303_06182_amd import binding, workloads as wl
 
     name = w.name
@@ -278,7 +378,7 @@ def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho, fmt=None):
                distinct_experts=len(set(e for t in trace for e in t)),
                all_resident=dict(ms_per_step=plain_ms, tokens_per_s=w.T / (plain_ms * 1e-3),
                                  expert_bytes_on_device=w.E * expert_bytes),
-               slots={}, simulated_miss_rate={})
+               slots={}, activity_trace=trace)
     for slots in slots_list:
         cache = (binding.ExpertCache(layer, slots, hw1, hw2, wbits, fmt["s1"], fmt["s2"]) if fmt
                  else binding.ExpertCache(layer, slots, hw1, hw2))
@@ -295,8 +395,6 @@ def _buffering_runs(w, g, hw1, hw2, slots_list, n_steps, rho, fmt=None):
             miss_rate=st["misses"] / max(1, st["hits"] + st["misses"]), bytes_copied=st["bytes_copied"],
             copy_GBps_over_wall_time=st["bytes_copied"] / secs / 1e9, stages_per_step=st["stages"] / n_steps,
             expert_bytes_on_device=slots * expert_bytes, device_bytes_saved=(w.E - slots) * expert_bytes)
-        out["simulated_miss_rate"][str(slots)] = {
-            pol: ec.simulate(trace, slots, pol)["miss_rate"] for pol in ec.POLICIES}
         del cache
         torch.cuda.empty_cache()
     return out
@@ -399,40 +497,69 @@ def yardsticks():
     return out
 
 
-def cpu_baseline(name, inp, budget_tokens):
-    """The CPU oracle as it stands, timed on the host cores on a bounded sample of the same
-    workload: the gate, top-k and routing for every token, the expert FFN and combine for
-    the first `budget_tokens` tokens (each output row depends only on its own token)."""
+def cpu_baseline(name, sample_tokens, seed=12345):
+    """The CPU oracle as it stands, timed on the host cores on a bounded sample of the same workload: the
+    gate, top-k and routing for EVERY token, the expert FFN and combine for `sample_tokens` tokens (each
+    output row depends only on its own token, so a sample is exact).  The sample holds, for every expert
+    with rows, the first and the last token routed to it, and is filled up with a seeded random choice."""
     import numpy as np
+    import torch
     from oracle import moe_oracle as orc
     from paper_2303_06182_amd import workloads as wl
 
     w = wl.CONFIGS[name]
-    n = min(w.T, budget_tokens)
+    inp = wl.make_inputs(w, device="cuda")
+    host = {k: (None if v is None else v.cpu()) for k, v in inp.items()}
+    del inp
+    torch.cuda.empty_cache()
+    n = min(w.T, sample_tokens)
     t0 = time.perf_counter()
-    logits = orc.gate_logits(inp["x"], inp["wg"], inp["gate_bias"])
+    logits = orc.gate_logits(host["x"], host["wg"], host["gate_bias"])
     idx, gw = orc.topk(logits, w.k)
-    orc.route(idx, w.E)
+    counts, offsets, dst_row, src_tok = orc.route(idx, w.E)
     t_route = time.perf_counter() - t0
+    must = set()
+    for e in range(w.E):
+        if counts[e] > 0:
+            must.add(int(src_tok[offsets[e]]))
+            must.add(int(src_tok[offsets[e + 1] - 1]))
+    rest = [int(t) for t in np.random.default_rng(seed).permutation(w.T) if int(t) not in must]
+    tokens = np.array(sorted(must) + rest[:max(0, n - len(must))], dtype=np.int32)
     t0 = time.perf_counter()
-    orc.layer_tokens(inp["x"], inp["w1"], inp["w2"], idx, gw, tokens=np.arange(n, dtype=np.int32))
+    orc.layer_tokens(host["x"], host["w1"], host["w2"], idx, gw, tokens=tokens)
     t_ffn = time.perf_counter() - t0
-    per_token = t_route / w.T + t_ffn / n
+    per_token = t_route / w.T + t_ffn / len(tokens)
+    experts_hit = len(set(idx[tokens].ravel().tolist()))
     return dict(value=1.0 / per_token, unit="tokens/s", cores=orc.n_threads(), kind="oracle",
-                sample="routing of all %d tokens (%.2f s) + expert FFN and combine of the first %d tokens "
-                       "(%.2f s), workload %s" % (w.T, t_route, n, t_ffn, name))
+                sample="workload %s: gate + top-k + routing of all %d tokens (%.2f s) + expert FFN and combine of "
+                       "%d tokens (%.2f s; seeded sample with every active expert's first and last token: %d of %d "
+                       "active experts hit), tokens/s = 1 / (routing s per token + FFN s per token)"
+                       % (name, w.T, t_route, len(tokens), t_ffn, experts_hit, int((counts > 0).sum())))
+
+
+def cpu_cache_policies(buffering):
+    """Part of the CPU-baseline leg: the oracle's cache simulator (paper policy, FIFO, LRU, Belady's MIN;
+    Sec. 6) on the expert-activity traces the expert-buffering runs observed."""
+    from oracle import expert_cache as ec
+    for run in buffering.values():
+        trace = run.get("activity_trace")
+        if trace is None:
+            continue
+        run["simulated_miss_rate"] = {slots: {pol: ec.simulate(trace, int(slots), pol)["miss_rate"]
+                                              for pol in ec.POLICIES} for slots in run["slots"]}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", default="lm")
-    ap.add_argument("--also", default="skewed_large,mt_encoder,mt_decoder,tiny_f32",
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="skewed_large", help="headline workload (default: the largest, skewed_large)")
+    ap.add_argument("--also", default="lm,mt_encoder,mt_decoder,tiny_f32",
                     help="comma list of further workloads reported under 'also' (the static baseline runs only "
-                         "for the headline workload and skewed_large)")
-    ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the CPU oracle's FFN sample (0 = skip)")
+                         "for the headline workload and lm)")
+    ap.add_argument("--cpu-tokens", type=int, default=16384,
+                    help="tokens of the CPU oracle's FFN sample (0 = skip the whole CPU-baseline leg)")
     ap.add_argument("--no-static", action="store_true", help="skip the static-capacity baseline runs")
     ap.add_argument("--no-buffering", action="store_true", help="skip the expert-buffering runs")
     ap.add_argument("--no-w8", action="store_true", help="skip the run with 8- and 4-bit expert weights (mt_decoder)")
@@ -448,7 +575,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2303_06182_amd import binding
+    from paper_2303_06182_amd import binding, workloads as wl
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
@@ -464,27 +591,39 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    main_res = run_config(args.config, args.steps, args.warmup, keep_host_copy=args.cpu_tokens > 0)
+    def cold_copies_for(name):
+        # enough copies of the weights to overflow the last-level cache twice, when one copy fits it
+        w = wl.CONFIGS[name]
+        wbytes = 2 * w.E * w.D * w.F * (2 if w.dtype == "bf16" else 4)
+        return 0 if wbytes > LAST_LEVEL_CACHE_BYTES else int(2 * LAST_LEVEL_CACHE_BYTES // wbytes) + 1
+
+    main_res = run_config(args.config, args.steps, args.warmup, cold_copies=cold_copies_for(args.config))
     also = {}
+    max_rows = {args.config: main_res["max_expert_rows"]}
     for name in [a for a in args.also.split(",") if a and a != args.config]:
-        r = run_config(name, max(5, args.steps // 5), max(2, args.warmup // 5), profile_steps=5)
+        r = run_config(name, args.steps, args.warmup, profile_steps=5, cold_copies=cold_copies_for(name))
+        max_rows[name] = r["max_expert_rows"]
         also[name] = dict(tokens_per_s=r["tokens_per_s"], ms_per_step=r["ms_per_step"], step_ms=r["step_ms"],
-                          working_set_bytes=r["working_set_bytes"], roofline=r["dominant"],
-                          kernels={k: dict(avg_ms=v["avg_ms"], bound=v["bound"], frac=v["frac"])
+                          working_set_bytes=r["working_set_bytes"], roofline=r["dominant"], cold=r["cold"],
+                          kernels={k: dict(avg_ms=v["avg_ms"], bound=v["bound"], frac=v["frac"], traffic=v["traffic"])
                                    for k, v in r["kernels"].items()},
                           max_expert_share=r["max_expert_share"])
     static = {}
     if not args.no_static:
-        static[args.config] = run_static(args.config, [1.0, 2.0])
-        for name in also:
-            if name == "skewed_large":
-                static[name] = run_static(name, [1.0, 2.0])
+        for name in [args.config] + [n for n in also if n == "lm"]:
+            static[name] = run_static(name, [1.0, 2.0], no_drop_rows=max_rows[name])
     buffering = None
     if not args.no_buffering:
         buffering = run_buffering("mt_decoder", [16, 48, 96], args.buffering_steps)
     w8 = None if args.no_w8 else run_weight_formats("mt_decoder")
     yard = None if args.no_yardsticks else yardsticks()
-    cpu = cpu_baseline(args.config, main_res["host"], args.cpu_tokens) if args.cpu_tokens > 0 else None
+    cpu = None
+    if args.cpu_tokens > 0:  # the CPU-baseline leg: the only part of this script that touches oracle/
+        cpu = cpu_baseline(args.config, args.cpu_tokens)
+        if buffering:
+            cpu_cache_policies(buffering)
+    for run in (buffering or {}).values():
+        run.pop("activity_trace", None)
 
     dom = dict(main_res["dominant"])
     out = {
@@ -504,12 +643,17 @@ def main():
         "config": {"workload": args.config, "T": main_res["T"], "D": main_res["D"], "F": main_res["F"],
                    "E": main_res["E"], "k": main_res["k"], "max_expert_share": main_res["max_expert_share"],
                    "idle_experts": main_res["idle_experts"], "workspace_bytes": main_res["workspace_bytes"],
-                   "working_set_bytes": main_res["working_set_bytes"]},
+                   "working_set_bytes": main_res["working_set_bytes"],
+                   "precondition_seconds": PRECONDITION_SECONDS, "precondition_steps": main_res["precondition_steps"]},
         "roofline": {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "avg_ms",
                                                 "algorithmic_bytes", "algorithmic_flops")},
         "cpu_baseline": cpu,
-        "kernels": {k: dict(avg_ms=v["avg_ms"], bound=v["bound"], achieved=v["achieved"], unit=v["unit"],
-                            frac=v["frac"], traffic=v["traffic"]) for k, v in main_res["kernels"].items()},
+        "kernels": {k: dict(avg_ms=v["avg_ms"], event_ms=v["event_ms"], bound=v["bound"], achieved=v["achieved"],
+                            unit=v["unit"], frac=v["frac"], traffic=v["traffic"],
+                            **({"in_fused_call": False} if not v.get("in_fused_call", True) else {}))
+                    for k, v in main_res["kernels"].items()},
+        "event_pair_overhead_ms": main_res["event_pair_overhead_ms"],
+        "cold": main_res["cold"],
         "also": also,
         "static_baseline": static,
         "expert_buffering": buffering,

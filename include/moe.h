@@ -107,7 +107,9 @@ const char *moe_last_error(void);
  * moe_profile_end is the one call of this library that WAITS for the device: it waits for the
  * recorded events, writes the elapsed milliseconds of record i to ms_out[i] (i < max_records),
  * stores the number of records in *n_records and switches profiling off.  moe_profile_name
- * gives the kernel name of record i ("" when out of range); valid until the next begin. */
+ * gives the kernel name of record i ("" when out of range); valid until the next begin.  The fused
+ * layer calls start with one record named "event_pair_overhead" that brackets no kernel at all: the
+ * time an event pair itself adds to each of the other records. */
 int moe_profile_begin(moe_handle_t *h);
 int moe_profile_end(moe_handle_t *h, float *ms_out, int32_t max_records, int32_t *n_records);
 const char *moe_profile_name(const moe_handle_t *h, int32_t i);

@@ -9,7 +9,7 @@ import torch
 
 from oracle import moe_oracle as orc
 from paper_2303_06182_amd import binding, workloads as wl
-from helpers import TOL, guarded_inputs, norm_max_err, to_np
+from helpers import RMS_TOL, TOL, guarded_inputs, norm_max_err, rms_rel_err, to_np
 
 pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -100,6 +100,49 @@ def test_static_example_with_the_papers_dimensions(mode):
         assert np.all(got[t] == 0.0)
     ref = orc.static_layer(x, wg, w1, w2, 1, cap)
     assert norm_max_err(got, ref["y"]) <= 1e-5
+
+
+def test_static_indexed_at_full_size_of_the_largest_workload():
+    """skewed_large at its real size through the static baseline (index-moved rows, capacity factor 1.0 = 1024
+    rows per expert: the configuration the benchmark times): slots and drops bit-exact for every assignment
+    against the static oracle, the output on a token sample that holds fully dropped, half dropped and fully
+    kept tokens."""
+    w = wl.CONFIGS["skewed_large"]
+    print("static full size", w, flush=True)
+    inp, _ = guarded_inputs(w, device="cuda")
+    m = binding.MoeLayer(w.T, w.D, w.F, w.E, w.k, w.dtype)
+    cap = binding.moe_capacity(w.T, w.E, w.k, 1.0, binding.MOE_CAPACITY_SHARE)
+    assert cap == 1024
+    r = m.empty_routing(w.T)
+    y, dropped = m.moe_layer_forward_static(inp["x"], inp["wg"], inp["w1"], inp["w2"], cap,
+                                            binding.MOE_STATIC_INDEXED, inp["gate_bias"], routing_out=r)
+    torch.cuda.synchronize()
+    host = {k: (None if v is None else v.cpu()) for k, v in inp.items()}
+    logits = orc.gate_logits(host["x"], host["wg"], host["gate_bias"])
+    idx, gw = orc.topk(logits, w.k)
+    slot, keep, n_dropped = orc.static_slots(idx, w.E, cap)
+    np.testing.assert_array_equal(to_np(r["topk_idx"]), idx)
+    np.testing.assert_array_equal(to_np(r["dst_row"]), np.where(keep == 1, idx * cap + slot, -1))
+    assert int(dropped[0]) == n_dropped and n_dropped > w.T // 2      # the skewed gate overflows the hot experts
+    kept = keep.sum(axis=1)
+    rng = np.random.default_rng(7)
+    tokens = np.concatenate([rng.choice(np.nonzero(kept == c)[0], size=min(700, int((kept == c).sum())), replace=False)
+                             for c in (0, 1, 2)])
+    # every expert's last kept row (slot cap - 1, or its last row when it is not full)
+    last = {}
+    for t, j in zip(*np.nonzero(keep == 1)):
+        last[int(idx[t, j])] = int(t)
+    tokens = np.union1d(tokens, np.array(sorted(last.values()))).astype(np.int32)
+    ref = orc.layer_tokens(host["x"], host["w1"], host["w2"], idx, gw, tokens=tokens, keep=keep)
+    got = to_np(y)[tokens]
+    assert np.all(np.isfinite(to_np(y)))
+    assert np.all(got[kept[tokens] == 0] == 0.0)                      # a fully dropped token leaves the layer as zero
+    err, rms = norm_max_err(got, ref), rms_rel_err(got, ref)
+    print("  static full size: dropped %d of %d, compared %d tokens, err %.3e rms %.3e" %
+          (n_dropped, w.k * w.T, tokens.size, err, rms), flush=True)
+    assert err <= TOL[w.dtype] and rms <= RMS_TOL[w.dtype]
+    del m, inp, y
+    torch.cuda.empty_cache()
 
 
 def test_static_workspace_and_argument_errors():
