@@ -35,7 +35,9 @@
  *     dimension, E experts, k experts per token, N = k*T assignments.
  *   - Inputs must be finite.  Expert indices handed to moe_route_counts must lie
  *     in [0,E); values outside are clamped into the range (memory safe, result
- *     then meaningless).
+ *     then meaningless).  The k experts of one token must be distinct, as top-k
+ *     selection makes them (Sec. 2.3); a token that names an expert twice still
+ *     gets two rows of that expert, in slot order, for any batch size.
  */
 #ifndef MOE355_MOE_H
 #define MOE355_MOE_H
@@ -133,8 +135,10 @@ int32_t moe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t convent
  *                        equal logits to the lower expert index
  *   topk_w[t,j] = gate weight of slot j (see moe_config_t.renormalize), fp32
  * x [T,D] elem, wg [E,D] elem, gate_bias [E] fp32 or NULL.  logits_out [T,E] fp32 may
- * be NULL only if `workspace` is given (the logits then live there).  workspace may be
- * NULL when logits_out is given.  T = 0 is a no-op. */
+ * be NULL only if `workspace` is given (kernels that need the logits in memory keep them
+ * there; for bf16, E <= 128, D a multiple of 64 and more than 256 tokens the decision is
+ * taken in the gate GEMM's epilogue and the logits are written only where logits_out asks
+ * for them).  workspace may be NULL when logits_out is given.  T = 0 is a no-op. */
 int moe_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias,
                   int32_t T, float *logits_out, int32_t *topk_idx, float *topk_w,
                   void *workspace, int64_t workspace_bytes, void *stream);

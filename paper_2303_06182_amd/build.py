@@ -15,7 +15,7 @@ OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe355.so")
 
 SOURCES = ["moe_api.hip", "route.hip", "permute.hip", "gemm_bf16.hip", "gemm_f32.hip", "static_baseline.hip",
-           "expert_cache.hip", "placement.hip", "quant.hip"]
+           "expert_cache.hip", "placement.hip", "quant.hip", "gate_topk.hip"]
 
 # packed fp32 instructions are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -150,7 +150,8 @@ static WsLayout ws_layout(const moe_config_t &c)
     L.offsets = take((E + 1) * 4);
     L.dst_row = take(N * 4);
     L.src_tok = take(N * 4);
-    L.block_hist = take((int64_t)route_blocks((int)T) * E * 4);
+    // one histogram row per 256 tokens (routing step) or per tile of the fused gate kernel (32 tokens at least)
+    L.block_hist = take(((T + 31) / 32 > route_blocks((int)T) ? (T + 31) / 32 : route_blocks((int)T)) * E * 4);
     const int64_t max_tiles = N / kMinBlockM + E + 1;
     L.tile_expert = take(max_tiles * 4);
     L.tile_row = take(max_tiles * 4);
@@ -253,13 +254,30 @@ static int validate_config(const moe_config_t *c)
 }
 
 // ---- the five steps ------------------------------------------------------------------------------
+// logits_req: where the caller wants the [T,E] logits, or NULL; logits_ws: room for them in the workspace, used
+// when a kernel needs them in memory and the caller did not ask (NULL only together with a non-NULL logits_req).
 // parts: room for (kGateSplitMax - 1) * min(T_max, kGateSplitTokens) * E floats, or NULL.  A decoder step's
 // gate GEMM (a tile or two, a long K loop) is cut along K into slices that the top-k kernel adds up.
+// hist != NULL: a kernel that decides the routing in the gate GEMM's epilogue may also leave the per-tile expert
+// histogram there (room for ceil(T / 32) * E int32); *hist_tokens then says how many tokens one row covers (0 =
+// no histogram was written and the routing step makes its own).
 static int do_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *gate_bias, int T,
-                        float *logits, int32_t *idx, float *w, hipStream_t s, float *parts = nullptr)
+                        float *logits_req, float *logits_ws, int32_t *idx, float *w, hipStream_t s,
+                        float *parts = nullptr, int32_t *hist = nullptr, int *hist_tokens = nullptr)
 {
     const moe_config_t &c = h->cfg;
+    if (hist_tokens) *hist_tokens = 0;
     if (T == 0) return MOE_OK;
+    // Batches beyond a decoder step, bf16, at most 128 experts: one kernel streams x, keeps the logits in
+    // registers and writes the decision (and the logits only where the caller asked for them).
+    if (T > kGateSplitTokens && gate_topk_fused_ok(c.dtype, T, c.E, c.D)) {
+        const bool want_hist = hist && hist_tokens && route_uses_hist(T, c.k);
+        int rc = launch_gate_topk(x, wg, gate_bias, T, c.E, c.D, c.k, c.renormalize, logits_req, idx, w,
+                                  want_hist ? hist : nullptr, h->num_cus, s);
+        if (rc == MOE_OK && want_hist) *hist_tokens = gate_topk_tile_tokens(T, c.E, h->num_cus);
+        return rc;
+    }
+    float *logits = logits_req ? logits_req : logits_ws;
     int split = 1;
     if (parts && c.dtype == MOE_DTYPE_BF16 && T <= kGateSplitTokens) {
         split = gemm_bf16_gate_split(T, c.E, c.D, h->num_cus);
@@ -643,18 +661,18 @@ int moe_gate_topk(moe_handle_t *h, const void *x, const void *wg, const float *g
     if (bad_ptr(x, "x") || bad_ptr(wg, "wg") || bad_ptr(gate_bias, "gate_bias", true) ||
         bad_ptr(logits_out, "logits_out", true) || bad_ptr(topk_idx, "topk_idx") || bad_ptr(topk_w, "topk_w"))
         return MOE_ERR_INVALID_ARG;
-    float *logits = logits_out;
-    if (!logits) {
+    const WsLayout L = ws_layout(h->cfg);
+    float *logits_ws = nullptr;
+    if (!logits_out) {
         rc = check_ws(h, workspace, workspace_bytes);
         if (rc != MOE_OK) return rc;
-        logits = at<float>(workspace, ws_layout(h->cfg).logits);
+        logits_ws = at<float>(workspace, L.logits);
     }
     // the split-K slices of a small batch's gate GEMM live in the workspace; without one the GEMM runs whole
-    const WsLayout L = ws_layout(h->cfg);
     float *parts = (workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0 && workspace_bytes >= L.total)
                        ? at<float>(workspace, L.gate_parts)
                        : nullptr;
-    return do_gate_topk(h, x, wg, gate_bias, T, logits, topk_idx, topk_w, (hipStream_t)stream, parts);
+    return do_gate_topk(h, x, wg, gate_bias, T, logits_out, logits_ws, topk_idx, topk_w, (hipStream_t)stream, parts);
 }
 
 int moe_route_counts(moe_handle_t *h, const int32_t *topk_idx, int32_t T, int32_t *counts, int32_t *offsets,
@@ -757,23 +775,24 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
     const moe_config_t &c = h->cfg;
     const WsLayout L = ws_layout(c);
     hipStream_t s = (hipStream_t)stream;
-    float *logits = r.logits ? r.logits : at<float>(workspace, L.logits);
     int32_t *idx = r.topk_idx ? r.topk_idx : at<int32_t>(workspace, L.topk_idx);
     float *w = r.topk_w ? r.topk_w : at<float>(workspace, L.topk_w);
     int32_t *counts = r.counts ? r.counts : at<int32_t>(workspace, L.counts);
     int32_t *offsets = r.offsets ? r.offsets : at<int32_t>(workspace, L.offsets);
     int32_t *dst_row = r.dst_row ? r.dst_row : at<int32_t>(workspace, L.dst_row);
     int32_t *src_tok = r.src_tok ? r.src_tok : at<int32_t>(workspace, L.src_tok);
+    int32_t *block_hist = at<int32_t>(workspace, L.block_hist);
     void *xp = at<void>(workspace, L.xp);
     void *yp = at<void>(workspace, L.yp);
 
-    if (empty) return launch_route(idx, 0, c.E, c.k, counts, offsets, dst_row, src_tok,
-                                   at<int32_t>(workspace, L.block_hist), s);
+    if (empty) return launch_route(idx, 0, c.E, c.k, counts, offsets, dst_row, src_tok, block_hist, s);
     {
         // an event pair around nothing: what the bracketing itself adds to every record of this call
         ProfScope nothing("event_pair_overhead", s);
     }
-    rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s, at<float>(workspace, L.gate_parts));
+    int hist_tokens = 0;  // > 0: the gate kernel has already left the expert histogram in block_hist
+    rc = do_gate_topk(h, x, wg, gate_bias, T, r.logits, at<float>(workspace, L.logits), idx, w, s,
+                      at<float>(workspace, L.gate_parts), block_hist, &hist_tokens);
     if (rc != MOE_OK) return rc;
     // the routing step's scan kernel also writes the first expert GEMM's tile map (not when the
     // experts are buffered: their tile maps are per stage)
@@ -782,9 +801,9 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
     const int bm1 = cache ? 0
                           : gemm_variant_block_m(c.dtype, wbits ? quant_variant(wbits, n_rows, c.E)
                                                                 : gemm_variant(c.dtype, n_rows, c.E, c.F, h->num_cus));
-    rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, at<int32_t>(workspace, L.block_hist), s, bm1,
+    rc = launch_route(idx, T, c.E, c.k, counts, offsets, dst_row, src_tok, block_hist, s, bm1,
                       at<int32_t>(workspace, L.tile_expert), at<int32_t>(workspace, L.tile_row),
-                      at<int32_t>(workspace, L.num_tiles), bm1 > 0 ? (int)(n_rows / bm1) + c.E + 1 : 0);
+                      at<int32_t>(workspace, L.num_tiles), bm1 > 0 ? (int)(n_rows / bm1) + c.E + 1 : 0, hist_tokens);
     if (rc != MOE_OK) return rc;
     // dispatch: a scatter of its own, or folded into the first GEMM's row addressing (then Xp is never written)
     const bool fused = fused_dispatch_ok(h, T, wbits);
@@ -1265,7 +1284,6 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
     }
     void *ws = workspace;
     const int64_t R = (int64_t)c.E * capacity;
-    float *logits = r.logits ? r.logits : at<float>(ws, L.logits);
     int32_t *idx = r.topk_idx ? r.topk_idx : at<int32_t>(ws, L.topk_idx);
     float *w = r.topk_w ? r.topk_w : at<float>(ws, L.topk_w);
     int32_t *counts_s = r.counts ? r.counts : at<int32_t>(ws, L.counts_s);
@@ -1278,7 +1296,7 @@ int moe_layer_forward_static(moe_handle_t *h, const void *x, const void *wg, con
     void *xd = at<void>(ws, L.xd);
     void *yd = at<void>(ws, L.yd);
 
-    rc = do_gate_topk(h, x, wg, gate_bias, T, logits, idx, w, s);
+    rc = do_gate_topk(h, x, wg, gate_bias, T, r.logits, at<float>(ws, L.logits), idx, w, s);
     if (rc != MOE_OK) return rc;
     // slot of every assignment = its rank inside its expert in slot-major order
     rc = launch_transpose_idx(idx, T, c.k, idx_t, dropped, s);

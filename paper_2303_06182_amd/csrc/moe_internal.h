@@ -156,9 +156,20 @@ int launch_topk(float *logits, int T, int E, int k, int renorm, int32_t *idx, fl
                 const float *parts = nullptr, int64_t part_stride = 0);
 // block_hist: scratch of route_blocks(T)*E int32
 int route_blocks(int T);
+// true when launch_route for T tokens with k experts each reads per-block histograms (large batches); small
+// ones are routed by one block that needs none
+bool route_uses_hist(int T, int k);
+// hist_tokens > 0: block_hist already holds one histogram row per hist_tokens tokens (a divisor of 256)
 int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,
                  int32_t *src_tok, int32_t *block_hist, hipStream_t s, int tile_bm = 0, int32_t *tile_expert = nullptr,
-                 int32_t *tile_row = nullptr, int32_t *num_tiles = nullptr, int max_m_tiles = 0);
+                 int32_t *tile_row = nullptr, int32_t *num_tiles = nullptr, int max_m_tiles = 0, int hist_tokens = 0);
+
+// Gate GEMM with softmax / top-k and the per-tile expert histogram in its epilogue (gate_topk.hip); bf16, E <= 128,
+// K a multiple of 64.  logits and hist may be NULL.  hist gets one row per gate_topk_tile_tokens() tokens.
+bool gate_topk_fused_ok(int dtype, int T, int E, int K);
+int gate_topk_tile_tokens(int T, int E, int num_cus);
+int launch_gate_topk(const void *x, const void *wg, const float *gate_bias, int T, int E, int K, int k, int renorm,
+                     float *logits, int32_t *idx, float *w, int32_t *hist, int num_cus, hipStream_t s);
 
 // ---- row movement --------------------------------------------------------------------------------
 int launch_dispatch(int dtype, const void *x, const int32_t *dst_row, int T, int D, int k, void *xp,

@@ -210,10 +210,12 @@ int launch_topk(float *logits, int T, int E, int k, int renorm, int32_t *idx, fl
 // ------------------------------------------------------------------------------------------------
 // counts / offsets / stable permutation.
 //   K1 route_hist : block b histograms its 256 tokens into LDS -> block_hist[b][e]
-//   K2 route_scan : per expert, exclusive prefix over the blocks (block_hist becomes the base of
-//                   block b inside expert e), counts[e], and offsets[] by a wave-shuffle scan
-//   K3 route_rank : block b ranks its tokens: ballot per expert inside a wave, LDS prefix over
-//                   the 4 waves, plus the block base and the expert offset
+//                   (the fused gate kernel writes these rows itself, one per tile of its own)
+//   K2 route_prefix: per expert (one wave each), exclusive prefix over the rows (block_hist becomes
+//                   the base of row b inside expert e) and counts[e]
+//   K3 route_rank : every block scans the counts into offsets[] (wave-shuffle scan), then ranks its
+//                   tokens: bit-wise ballots find equal experts inside a wave, an LDS prefix runs over
+//                   the 4 waves, plus the row base and the expert offset
 // ------------------------------------------------------------------------------------------------
 int route_blocks(int T) { return T > 0 ? ceil_div(T, kThreads) : 1; }
 
@@ -233,47 +235,47 @@ __global__ __launch_bounds__(kThreads) void route_hist_kernel(const int32_t *__r
     for (int e = threadIdx.x; e < E; e += kThreads) block_hist[(int64_t)blockIdx.x * E + e] = hist[e];
 }
 
-// One block of 1024 threads.  Threads are laid out [segment][expert]: EP = E rounded up to a
-// power of two (>= 1), S = 1024 / EP segments, each covering a contiguous range of blocks.
-// tile_bm > 0: also emits the grouped GEMM's M-tile map for tiles of tile_bm rows (what
-// tile_map_kernel computes from the offsets), saving that launch in the fused layer call.
-__global__ __launch_bounds__(1024) void route_scan_kernel(int32_t *__restrict__ block_hist, int nblk, int E, int EP,
-                                                          int total, int32_t *__restrict__ counts,
-                                                          int32_t *__restrict__ offsets, int tile_bm,
-                                                          int32_t *__restrict__ tile_expert,
-                                                          int32_t *__restrict__ tile_row,
-                                                          int32_t *__restrict__ num_tiles, int max_m_tiles)
+// Per expert, the exclusive prefix of its histogram column over the rows (blocks of tokens) and its total.
+// One wave per expert, 64 rows per step: the column is walked with a wave-shuffle scan and a running carry.
+// hist[b][e] becomes the number of assignments to expert e in the rows before b.
+__global__ __launch_bounds__(kThreads) void route_prefix_kernel(int32_t *__restrict__ hist, int nrows, int E,
+                                                                int32_t *__restrict__ counts)
 {
-    __shared__ int seg_sum[1024];
-    __shared__ int wave_tot[16];
-    const int S = 1024 / EP;
-    const int e = threadIdx.x % EP;
-    const int seg = threadIdx.x / EP;
-    const int per = ceil_div(nblk, S);
-    const int b0 = seg * per;
-    const int b1 = min(nblk, b0 + per);
-    int sum = 0;
-    if (e < E)
-        for (int b = b0; b < b1; ++b) sum += block_hist[(int64_t)b * E + e];
-    seg_sum[threadIdx.x] = sum;
-    __syncthreads();
-    int base = 0;
-    for (int s2 = 0; s2 < seg; ++s2) base += seg_sum[s2 * EP + e];
-    if (e < E) {
-        int run = base;
-        for (int b = b0; b < b1; ++b) {
-            const int v = block_hist[(int64_t)b * E + e];
-            block_hist[(int64_t)b * E + e] = run;
-            run += v;
+    const int lane = threadIdx.x % kWave;
+    const int e = blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+    if (e >= E) return;  // whole waves leave together
+    int carry = 0;
+    for (int b0 = 0; b0 < nrows; b0 += kWave) {
+        const int b = b0 + lane;
+        const int v = b < nrows ? hist[(int64_t)b * E + e] : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
         }
+        if (b < nrows) hist[(int64_t)b * E + e] = carry + incl - v;
+        carry += __shfl(incl, kWave - 1, kWave);
     }
-    // counts of expert `threadIdx.x` (threads 0..E-1), then exclusive scan over the experts
-    int cnt = 0;
-    if (threadIdx.x < E)
-        for (int s2 = 0; s2 < S; ++s2) cnt += seg_sum[s2 * EP + threadIdx.x];
-    int incl = cnt;
+    if (lane == 0) counts[e] = carry;
+}
+
+// Exclusive scan of n <= 4 * blockDim values in LDS (in place), one block; returns nothing, `total` receives
+// the sum.  Thread t owns elements 4 t .. 4 t + 3.
+__device__ __forceinline__ void block_exclusive_scan4(int *vals, int n, int *wave_tot, int &total)
+{
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
+    const int nw = blockDim.x / kWave;
+    int loc[4];
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int at = 4 * threadIdx.x + i;
+        loc[i] = at < n ? vals[at] : 0;
+        sum += loc[i];
+    }
+    int incl = sum;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
         const int up = __shfl_up(incl, off, kWave);
@@ -281,73 +283,103 @@ __global__ __launch_bounds__(1024) void route_scan_kernel(int32_t *__restrict__ 
     }
     if (lane == kWave - 1) wave_tot[wave] = incl;
     __syncthreads();
-    int wbase = 0;
-    for (int w2 = 0; w2 < wave; ++w2) wbase += wave_tot[w2];
-    const int my_off = wbase + incl - cnt;
-    if (threadIdx.x < E) {
-        counts[threadIdx.x] = cnt;
-        offsets[threadIdx.x] = my_off;
+    int run = incl - sum;
+    int all = 0;
+    for (int w2 = 0; w2 < nw; ++w2) {
+        const int t = wave_tot[w2];
+        if (w2 < wave) run += t;
+        all += t;
     }
-    if (threadIdx.x == 0) offsets[E] = total;
-    if (tile_bm > 0) {  // uniform over the block
-        const int nt = (threadIdx.x < E && cnt > 0) ? (cnt + tile_bm - 1) / tile_bm : 0;
-        int incl_t = nt;
+    total = all;
 #pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int up = __shfl_up(incl_t, off, kWave);
-            if (lane >= off) incl_t += up;
-        }
-        __syncthreads();  // wave_tot is reused
-        if (lane == kWave - 1) wave_tot[wave] = incl_t;
-        __syncthreads();
-        int tbase = 0;
-        for (int w2 = 0; w2 < wave; ++w2) tbase += wave_tot[w2];
-        const int first = tbase + incl_t - nt;
-        for (int i = 0; i < nt; ++i) {
-            const int ti = first + i;
-            if (ti < max_m_tiles) {
-                tile_expert[ti] = threadIdx.x;
-                tile_row[ti] = my_off + i * tile_bm;
-            }
-        }
-        if (threadIdx.x == 1023) num_tiles[0] = min(first + nt, max_m_tiles);
+    for (int i = 0; i < 4; ++i) {
+        const int at = 4 * threadIdx.x + i;
+        if (at < n) vals[at] = run;
+        run += loc[i];
     }
+    __syncthreads();
 }
 
+// Stable position of every assignment.  Block b ranks its 256 tokens:
+//   row(t, j) = offsets[e] + (assignments to e in the blocks before b) + (in the waves before this one)
+//               + (in the lanes before this one, or in earlier slots of this lane)
+// Every block scans the E counts into the offsets itself (E <= 1024 integers out of L2), so no launch stands
+// between the per-expert prefix and the ranking; block 0 also writes offsets[] and, when asked, the grouped
+// GEMM's M-tile map.
+// Equal experts inside a wave are found with one ballot per BIT of the expert index (ceil(log2 E) of them
+// per slot) instead of one per expert: the lanes whose slot j' holds this lane's expert are the AND over the
+// bits b of (bit b of my expert set ? ballot(bit b set) : its complement).
+// hist_row_step: histogram rows per block of 256 tokens (the fused gate kernel's tiles may be shorter).
 template <int KMAX>
 __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__restrict__ idx, int T, int E, int k,
-                                                              const int32_t *__restrict__ offsets,
+                                                              int nbits, const int32_t *__restrict__ counts,
                                                               const int32_t *__restrict__ block_base,
+                                                              int hist_row_step, int32_t *__restrict__ offsets,
                                                               int32_t *__restrict__ dst_row,
-                                                              int32_t *__restrict__ src_tok)
+                                                              int32_t *__restrict__ src_tok, int tile_bm,
+                                                              int32_t *__restrict__ tile_expert,
+                                                              int32_t *__restrict__ tile_row,
+                                                              int32_t *__restrict__ num_tiles, int max_m_tiles)
 {
     constexpr int NW = kThreads / kWave;
+    __shared__ int offs[MOE_MAX_E];
     __shared__ int wave_cnt[NW][MOE_MAX_E];
+    __shared__ int wave_tot[NW];
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
     const int t = blockIdx.x * kThreads + threadIdx.x;
+
+    for (int e = threadIdx.x; e < E; e += kThreads) {
+        offs[e] = counts[e];
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) wave_cnt[w2][e] = 0;
+    }
+    __syncthreads();
+    int total = 0;
+    block_exclusive_scan4(offs, E, wave_tot, total);  // offs[e] = first row of expert e
+    if (blockIdx.x == 0) {
+        for (int e = threadIdx.x; e < E; e += kThreads) offsets[e] = offs[e];
+        if (threadIdx.x == 0) offsets[E] = total;
+    }
+
     int ej[KMAX];
-    int rank[KMAX];
+    int below[KMAX];  // assignments to the same expert earlier in this wave
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
         ej[j] = (t < T && j < k) ? clamp_expert(idx[(int64_t)t * k + j], E) : -1;
-        rank[j] = 0;
+        below[j] = 0;
     }
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
-    for (int e = 0; e < E; ++e) {
-        int slot = -1;
+    const uint64_t gt_mask = (lane == kWave - 1) ? 0ull : (~0ull << (lane + 1));
+    int after[KMAX];  // ... later in this wave
 #pragma unroll
-        for (int j = 0; j < KMAX; ++j)
-            if (ej[j] == e) slot = j;
-        const uint64_t mask = __ballot(slot >= 0);
-        if (slot >= 0) {
-            const int r = __popcll(mask & lt_mask);
+    for (int j = 0; j < KMAX; ++j) after[j] = 0;
 #pragma unroll
-            for (int j = 0; j < KMAX; ++j)
-                if (j == slot) rank[j] = r;
+    for (int jp = 0; jp < KMAX; ++jp) {
+        if (jp >= k) continue;  // uniform
+        uint64_t same[KMAX];
+        const uint64_t valid = __ballot(ej[jp] >= 0);
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) same[j] = valid;
+        for (int b = 0; b < nbits; ++b) {
+            const uint64_t bal = __ballot(ej[jp] >= 0 && ((ej[jp] >> b) & 1));
+#pragma unroll
+            for (int j = 0; j < KMAX; ++j) same[j] &= ((ej[j] >> b) & 1) ? bal : ~bal;
         }
-        if (lane == 0) wave_cnt[wave][e] = __popcll(mask);
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+            if (ej[j] < 0) continue;
+            below[j] += __popcll(same[j] & lt_mask);
+            after[j] += __popcll(same[j] & gt_mask);
+            // the lane's own other slots (only a caller's duplicate experts make these match)
+            if (jp < j && ej[jp] == ej[j]) below[j] += 1;
+            if (jp > j && ej[jp] == ej[j]) after[j] += 1;
+        }
     }
+    // the last assignment of every expert present in the wave publishes the wave's count of it
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j)
+        if (ej[j] >= 0 && after[j] == 0) wave_cnt[wave][ej[j]] = below[j] + 1;
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += kThreads) {
         int run = 0;
@@ -360,15 +392,35 @@ __global__ __launch_bounds__(kThreads) void route_rank_kernel(const int32_t *__r
     }
     __syncthreads();
     if (t < T) {
+        const int32_t *base = block_base + (int64_t)blockIdx.x * hist_row_step * E;
 #pragma unroll
         for (int j = 0; j < KMAX; ++j) {
             if (j < k) {
                 const int e = ej[j];
-                const int r = offsets[e] + block_base[(int64_t)blockIdx.x * E + e] + wave_cnt[wave][e] + rank[j];
+                const int r = offs[e] + base[e] + wave_cnt[wave][e] + below[j];
                 dst_row[(int64_t)t * k + j] = r;
                 src_tok[r] = t;
             }
         }
+    }
+    if (tile_bm > 0 && blockIdx.x == 0) {  // the grouped GEMM's M-tile map: expert e owns ceil(count / tile_bm) tiles
+        __syncthreads();
+        int *first = &wave_cnt[0][0];  // reused: first tile of every expert
+        for (int e = threadIdx.x; e < E; e += kThreads) first[e] = (counts[e] + tile_bm - 1) / tile_bm;
+        __syncthreads();
+        int n_tiles = 0;
+        block_exclusive_scan4(first, E, wave_tot, n_tiles);
+        for (int e = threadIdx.x; e < E; e += kThreads) {
+            const int nt = (counts[e] + tile_bm - 1) / tile_bm;
+            for (int i = 0; i < nt; ++i) {
+                const int ti = first[e] + i;
+                if (ti < max_m_tiles) {
+                    tile_expert[ti] = e;
+                    tile_row[ti] = offs[e] + i * tile_bm;
+                }
+            }
+        }
+        if (threadIdx.x == 0) num_tiles[0] = min(n_tiles, max_m_tiles);
     }
 }
 
@@ -496,41 +548,50 @@ __global__ __launch_bounds__(1024) void route_small_kernel(const int32_t *__rest
     }
 }
 
+bool route_uses_hist(int T, int k) { return (int64_t)T * k > kSmallRouteMax; }
+
 int launch_route(const int32_t *idx, int T, int E, int k, int32_t *counts, int32_t *offsets, int32_t *dst_row,
                  int32_t *src_tok, int32_t *block_hist, hipStream_t s, int tile_bm, int32_t *tile_expert,
-                 int32_t *tile_row, int32_t *num_tiles, int max_m_tiles)
+                 int32_t *tile_row, int32_t *num_tiles, int max_m_tiles, int hist_tokens)
 {
-    const int nblk = route_blocks(T);
-    int EP = 1;
-    while (EP < E) EP <<= 1;
-    ProfScope ps("route", s);  // histogram + scan + rank together
+    ProfScope ps("route", s);  // histogram + prefix + rank together
     if ((int64_t)T * k <= kSmallRouteMax) {
         hipLaunchKernelGGL(route_small_kernel, dim3(1), dim3(1024), 0, s, idx, T * k, E, k, counts, offsets, dst_row,
                            src_tok, tile_bm, tile_expert, tile_row, num_tiles, max_m_tiles);
         MOE_LAUNCH_CHECK("route_small_kernel");
         return MOE_OK;
     }
-    hipLaunchKernelGGL(route_hist_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, block_hist);
-    MOE_LAUNCH_CHECK("route_hist_kernel");
-    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), 0, s, block_hist, nblk, E, EP, T * k, counts, offsets,
-                       tile_bm, tile_expert, tile_row, num_tiles, max_m_tiles);
-    MOE_LAUNCH_CHECK("route_scan_kernel");
-    if (T > 0) {
-        // KMAX = slots a lane compares per expert: the smallest instantiation that holds k
-        if (k <= 1)
-            hipLaunchKernelGGL(route_rank_kernel<1>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
-                               block_hist, dst_row, src_tok);
-        else if (k <= 2)
-            hipLaunchKernelGGL(route_rank_kernel<2>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
-                               block_hist, dst_row, src_tok);
-        else if (k <= 4)
-            hipLaunchKernelGGL(route_rank_kernel<4>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
-                               block_hist, dst_row, src_tok);
-        else
-            hipLaunchKernelGGL(route_rank_kernel<MOE_MAX_K>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, offsets,
-                               block_hist, dst_row, src_tok);
-        MOE_LAUNCH_CHECK("route_rank_kernel");
+    // hist_tokens > 0: block_hist already holds one histogram row per hist_tokens tokens (the fused gate kernel
+    // wrote it); else it is made here, one row per block of 256 tokens
+    if (hist_tokens > 0 && (kThreads % hist_tokens != 0)) {
+        set_error("route: %d tokens per histogram row do not divide %d", hist_tokens, kThreads);
+        return MOE_ERR_INVALID_ARG;
     }
+    const int nblk = route_blocks(T);
+    int nrows = nblk, row_step = 1;
+    if (hist_tokens > 0) {
+        nrows = ceil_div(T, hist_tokens);
+        row_step = kThreads / hist_tokens;
+    } else {
+        hipLaunchKernelGGL(route_hist_kernel, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, block_hist);
+        MOE_LAUNCH_CHECK("route_hist_kernel");
+    }
+    hipLaunchKernelGGL(route_prefix_kernel, dim3(ceil_div(E, kThreads / kWave)), dim3(kThreads), 0, s, block_hist,
+                       nrows, E, counts);
+    MOE_LAUNCH_CHECK("route_prefix_kernel");
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+#define MOE_RANK(KM)                                                                                              \
+    hipLaunchKernelGGL(route_rank_kernel<KM>, dim3(nblk), dim3(kThreads), 0, s, idx, T, E, k, nbits, counts,      \
+                       block_hist, row_step, offsets, dst_row, src_tok, tile_bm, tile_expert, tile_row, num_tiles, \
+                       max_m_tiles)
+    // KMAX = slots a lane holds: the smallest instantiation that holds k
+    if (k <= 1) MOE_RANK(1);
+    else if (k <= 2) MOE_RANK(2);
+    else if (k <= 4) MOE_RANK(4);
+    else MOE_RANK(MOE_MAX_K);
+#undef MOE_RANK
+    MOE_LAUNCH_CHECK("route_rank_kernel");
     return MOE_OK;
 }
 

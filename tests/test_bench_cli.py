@@ -38,7 +38,7 @@ def test_roofline_traffic_is_what_the_committed_profiles_say():
     import bench
     from paper_2303_06182_amd import workloads as wl
     prof_dir = os.path.join(ROOT, "profiles")
-    known = {"gate_gemm", "topk", "route", "dispatch", "expert_gemm1", "expert_gemm2", "combine", "tile_map"}
+    known = {"gate_gemm", "gate_topk", "topk", "route", "dispatch", "expert_gemm1", "expert_gemm2", "combine", "tile_map"}
     seen = 0
     for fname in sorted(os.listdir(prof_dir)):
         if not (fname.startswith("moe_layer_forward_") and fname.endswith(".txt")):

@@ -86,6 +86,16 @@ GATE_CASES = [
     ("bf16_splitk_e128", "bf16", 100, 1024, 128, 2, True, 0.0, 30.0),
     ("bf16_splitk_e37", "bf16", 33, 2048, 37, 3, False, 0.0, 30.0),
     ("bf16_splitk_t1", "bf16", 1, 4096, 16, 2, True, 0.0, 30.0),
+    # more than 256 tokens, bf16, E <= 128, D a multiple of 64: the gate GEMM decides the routing in its epilogue.
+    # Tile heights 32 / 64 / 128 / 256 rows (by T), 1 to 4 column blocks (by E), E not a multiple of 4 or 32,
+    # k = 1 .. 8, raw softmax, a ragged last tile
+    ("bf16_fused_e37_k3", "bf16", 3001, 192, 37, 3, False, 0.0, 40.0),
+    ("bf16_fused_e8_k8", "bf16", 600, 64, 8, 8, True, 0.0, 40.0),
+    ("bf16_fused_e96_t33k", "bf16", 33000, 128, 96, 2, True, 1.0, 40.0),
+    ("bf16_fused_e8_t70k", "bf16", 70001, 64, 8, 1, True, 0.0, 40.0),
+    ("bf16_fused_e64_t66k_k4", "bf16", 66000, 64, 64, 4, False, 0.8, 40.0),
+    ("bf16_fused_e128_t17k", "bf16", 17000, 256, 128, 2, True, 1.2, 40.0),
+    ("bf16_fused_e100_k5", "bf16", 9000, 128, 100, 5, True, 0.0, 40.0),
 ]
 
 
@@ -144,6 +154,32 @@ def test_route_counts_bit_exact(dev, T, E, k, skew):
     np.testing.assert_array_equal(to_np(offsets), ro)
     np.testing.assert_array_equal(to_np(dst_row), rd)
     np.testing.assert_array_equal(to_np(src_tok), rs)
+
+
+@pytest.mark.parametrize("T", [700, 5000])   # below and above the single-block kernel's 4096 assignments
+def test_route_with_a_repeated_expert_inside_a_token(dev, T):
+    """The k experts of a token are distinct by construction (top-k selection, Sec. 2.3); handed a token that
+    names one expert twice, the routing still has to be a permutation -- both kernels rank such assignments
+    in (token, slot) order -- and everything around it must equal the oracle."""
+    E, k = 16, 2
+    idx = random_idx(T, E, k, seed=T, skew=True)
+    dup = [3, T // 2, T - 1]
+    idx[dup, 1] = idx[dup, 0]
+    m = binding.MoeLayer(T, 64, 64, E, k, "bf16")
+    counts, offsets, dst_row, src_tok = [to_np(a) for a in m.moe_route_counts(torch.from_numpy(idx).cuda())]
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(counts, np.bincount(idx.ravel(), minlength=E))
+    np.testing.assert_array_equal(offsets, np.concatenate([[0], np.cumsum(counts)]))
+    assert sorted(dst_row.ravel().tolist()) == list(range(T * k))           # a bijection onto the rows
+    for t in range(T):
+        for j in range(k):
+            r = dst_row[t, j]
+            assert offsets[idx[t, j]] <= r < offsets[idx[t, j] + 1] and src_tok[r] == t
+    for t in dup:
+        assert dst_row[t, 1] == dst_row[t, 0] + 1                          # slot order inside the token
+    for e in range(E):                                                     # ascending tokens inside an expert
+        rows = src_tok[offsets[e]:offsets[e + 1]]
+        assert np.all(np.diff(rows) >= 0)
 
 
 def test_route_all_tokens_to_one_expert_and_T_zero(dev):
