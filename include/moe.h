@@ -355,7 +355,9 @@ int moe_expert_cache_stats(const moe_expert_cache_t *c, int64_t *hits, int64_t *
  * their slots on the cache's copy stream while the experts that are already resident compute, and
  * the expert FFN runs stage by stage (see moe_cache_policy_step) from the slots.  b1 [E,F] and
  * b2 [E,D] (NULL or device memory) are not buffered.  Needs `slots` >= 1; a batch with more active
- * experts than slots runs in several stages.  Calls on one cache must not overlap. */
+ * experts than slots runs in several stages.  Calls on one cache must not overlap.  If the call fails after
+ * the cache decision was taken (a copy or a launch reports an error), the cache forgets every resident expert
+ * (hit / miss statistics are zeroed with it), so the next call reloads what it needs. */
 int moe_layer_forward_buffered(moe_handle_t *h, moe_expert_cache_t *cache, const void *x, const void *wg,
                                const float *gate_bias, const void *b1, const void *b2, int32_t T, void *y,
                                const moe_routing_t *routing_out, void *workspace, int64_t workspace_bytes,

@@ -48,7 +48,7 @@
 // together share A rows and B (weight) rows.  The load cursor walks the block's whole sequence of (tile, K tile)
 // pairs, so the first K tiles of the NEXT tile are loaded during the last iterations of the current
 // one: the pipeline never drains between tiles and the epilogue's stores overlap the next tile.
-#include <stdlib.h>
+#include <mutex>
 
 #include "moe_internal.h"
 
@@ -922,14 +922,18 @@ static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *mai
     const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (BQ == 8 ? BN / 2 : BQ == 4 ? BN / 4 : BN)) * BK * sizeof(uint16_t) +
                         (BQ == 4 ? 2 * BN * 16 : 0);  // 4-bit weights: two buffers of block scales
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES, BQ>;
-    static int blocks_per_cu = 0;  // per instantiation
-    if (blocks_per_cu == 0) {
-        MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    // per instantiation, once, whichever host thread comes first: the LDS size attribute and the occupancy
+    static std::once_flag once;
+    static int blocks_per_cu = 0;
+    static hipError_t setup_rc = hipSuccess;
+    std::call_once(once, [&]() {
+        setup_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)smem);
         int occ = 0;
-        MOE_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, WM * WN * 64, smem));
+        if (setup_rc == hipSuccess) setup_rc = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, WM * WN * 64, smem);
         blocks_per_cu = occ < 1 ? 1 : (occ > 8 ? 8 : occ);
-    }
+    });
+    MOE_HIP_CHECK(setup_rc);
     // persistent grid: every resident slot of the chip, but never more blocks than upper-bound tiles
     int64_t grid = (int64_t)num_cus * blocks_per_cu;
     int64_t tiles = (int64_t)m_tiles * n_tiles;
@@ -979,32 +983,10 @@ static int launch_grouped_w8(const GemmParams &p, bool relu, int num_cus, hipStr
 
 // Tile shapes of the grouped GEMM.  variant -> (BM, BN, waves, pipeline)
 //   8: 256x256, 8 waves, register-staged    10: 128x128, 4 waves, register-staged
-//   5: 256x256, 8 waves, direct-to-LDS       1: 128x128, 4 waves, direct-to-LDS
 //   2: 64x128, 4 waves, direct-to-LDS        3: 32x128, 4 waves, direct-to-LDS
-// The automatic choice goes by the average number of rows per expert; 5 and 1 are kept for
-// comparison runs.  (A 128x256 shape, meant to quantise better over the CUs when a GEMM has only
-// one or two 256x256 tiles per CU, measured 16 % slower per flop and lost even there.)
-static int forced_variant()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("MOE355_GEMM_VARIANT");  // tuning override, 0 / unset = automatic
-        v = e ? atoi(e) : 0;
-        if (v != 1 && v != 2 && v != 3 && v != 5 && v != 8 && v != 10) v = 0;
-    }
-    return v;
-}
-
-static bool no_tail_split()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("MOE355_GEMM_NO_TAIL_SPLIT");  // comparison runs
-        v = (e && atoi(e) != 0) ? 1 : 0;
-    }
-    return v == 1;
-}
-
+// The choice goes by the average number of rows per expert.  (Direct-to-LDS forms of the two large shapes
+// measured 7-8 % slower than the register-staged ones; a 128x256 shape, meant to quantise better over the
+// CUs when a GEMM has only one or two 256x256 tiles per CU, measured 16 % slower per flop and lost even there.)
 // every grouped bf16 shape reads A through per-lane row pointers when K is a multiple of the K tile
 bool gemm_bf16_variant_gathers(int variant, int K) { return variant != 0 && K % BK == 0; }
 
@@ -1014,13 +996,6 @@ bool gemm_bf16_variant_gathers(int variant, int K) { return variant != 0 && K % 
 // CU all land within +-8 % of these two; deeper pipelines lose blocks per CU and are slower.)
 int gemm_bf16_variant_w8(int64_t n_rows, int E)
 {
-    static int forced = -1;
-    if (forced < 0) {
-        const char *e = getenv("MOE355_W8_VARIANT");  // tuning override, 0 / unset = automatic
-        forced = e ? atoi(e) : 0;
-        if (forced != 22 && forced != 23) forced = 0;
-    }
-    if (forced) return forced;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
     return avg >= 48 ? 22 : 23;
 }
@@ -1035,13 +1010,6 @@ int gemm_bf16_variant_w8(int64_t n_rows, int E)
 // would shorten it.)
 int gemm_bf16_variant_w4(int64_t n_rows, int E)
 {
-    static int forced = -1;
-    if (forced < 0) {
-        const char *e = getenv("MOE355_W4_VARIANT");  // tuning override, 0 / unset = automatic
-        forced = e ? atoi(e) : 0;
-        if (forced != 43 && forced != 48) forced = 0;
-    }
-    if (forced) return forced;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
     return avg >= 96 ? 48 : 43;
 }
@@ -1064,7 +1032,7 @@ int gemm_bf16_gate_split(int M, int N, int K, int num_cus)
 int gemm_bf16_variant_block_m(int v)
 {
     switch (v) {
-    case 1: case 10: return 128;
+    case 10: return 128;
     case 2: case 22: case 48: return 64;
     case 3: case 23: case 43: return 32;
     default: return 256;
@@ -1075,8 +1043,6 @@ int gemm_bf16_variant(int64_t n_rows, int E, int N, int num_cus)
 {
     (void)N;
     (void)num_cus;
-    const int f = forced_variant();
-    if (f) return f;
     const int64_t avg = E > 0 ? n_rows / E : n_rows;
     if (avg >= 192) return 8;
     if (avg >= 96) return 10;
@@ -1123,7 +1089,7 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
     switch (variant) {
     case 8: {
         // whole rounds as 256x256 tiles, the partly filled last round as 128x128 sub-tiles
-        if (p.K % BK != 0 || no_tail_split()) return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
+        if (p.K % BK != 0) return launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(p, relu, num_cus, s);
         GemmParams q = p;
         int main_grid = 0;
         q.tail_mode = 1;
@@ -1133,8 +1099,6 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
         return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(q, relu, num_cus, s, &main_grid);
     }
     case 10: return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(p, relu, num_cus, s);
-    case 5: return launch_grouped<256, 256, 2, 4, 1>(p, relu, num_cus, s);
-    case 1: return launch_grouped<128, 128, 2, 2, 2>(p, relu, num_cus, s);
     case 22: return launch_grouped_w8<64, 128, 1, 4, 2, 3>(p, relu, num_cus, s);
     case 23: return launch_grouped_w8<32, 128, 1, 4, 2, 4>(p, relu, num_cus, s);
     case 43: return launch_grouped_w8<32, 256, 1, 4, 2, 3, 4>(p, relu, num_cus, s);

@@ -409,13 +409,8 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
 // Can the first expert GEMM gather its rows from the token array (T tokens) itself?
 static bool fused_dispatch_ok(const moe_handle_t *h, int64_t T, int wbits = 0)
 {
-    static int off = -1;
-    if (off < 0) {
-        const char *e = getenv("MOE355_NO_FUSED_DISPATCH");  // comparison runs
-        off = (e && atoi(e) != 0) ? 1 : 0;
-    }
     const moe_config_t &c = h->cfg;
-    if (off || c.dtype != MOE_DTYPE_BF16 || T * c.D >= ((int64_t)1 << 31)) return false;
+    if (c.dtype != MOE_DTYPE_BF16 || T * c.D >= ((int64_t)1 << 31)) return false;
     const int v = wbits ? quant_variant(wbits, T * c.k, c.E) : gemm_variant(c.dtype, T * c.k, c.E, c.F, h->num_cus);
     return gemm_bf16_variant_gathers(v, c.D);
 }
@@ -1076,7 +1071,11 @@ int moe_expert_cache_create_q(moe_handle_t *h, int32_t slots, int32_t wbits, con
     k->stage_of.assign(c.E, -1);
     k->loads.assign((size_t)4 * c.E, 0);
     int rc = moe_cache_policy_create(c.E, slots, &k->policy);
-    if (rc == MOE_OK && hipSetDevice(h->device) != hipSuccess) rc = hip_failed(hipGetLastError(), "hipSetDevice");
+    // the copy stream and the pinned block belong to the handle's device; the caller's current device is put back
+    int prev_dev = -1;
+    if (rc == MOE_OK && hipGetDevice(&prev_dev) != hipSuccess) rc = hip_failed(hipGetLastError(), "hipGetDevice");
+    if (rc == MOE_OK && prev_dev != h->device && hipSetDevice(h->device) != hipSuccess)
+        rc = hip_failed(hipGetLastError(), "hipSetDevice");
     if (rc == MOE_OK) {
         hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&k->pin), (size_t)3 * c.E * 4, hipHostMallocDefault);
         if (e != hipSuccess) rc = hip_failed(e, "hipHostMalloc");
@@ -1085,6 +1084,7 @@ int moe_expert_cache_create_q(moe_handle_t *h, int32_t slots, int32_t wbits, con
         hipError_t e = hipStreamCreateWithFlags(&k->copy_stream, hipStreamNonBlocking);
         if (e != hipSuccess) rc = hip_failed(e, "hipStreamCreateWithFlags");
     }
+    if (prev_dev >= 0 && prev_dev != h->device) (void)hipSetDevice(prev_dev);
     if (rc != MOE_OK) {
         moe_expert_cache_destroy(k);
         return rc;
@@ -1136,9 +1136,31 @@ int moe_expert_cache_stats(const moe_expert_cache_t *k, int64_t *hits, int64_t *
 //   policy stage: the stage's missing experts are copied on the copy stream (after everything that
 //   ran in earlier stages, whose slots they may take), the stage's resident experts compute
 //   meanwhile on the caller's stream, and the copied ones follow once their copy has landed.
+static int buffered_expert_ffn_run(moe_handle_t *h, moe_expert_cache_t *k, const void *xin, const int32_t *a_rows,
+                                   const int32_t *counts, const int32_t *offsets, const void *b1, const void *b2,
+                                   int32_t n_rows, void *yp, void *workspace, hipStream_t s, bool *policy_advanced);
+
 static int buffered_expert_ffn(moe_handle_t *h, moe_expert_cache_t *k, const void *xin, const int32_t *a_rows,
                                const int32_t *counts, const int32_t *offsets, const void *b1, const void *b2,
                                int32_t n_rows, void *yp, void *workspace, hipStream_t s)
+{
+    bool policy_advanced = false;
+    const int rc = buffered_expert_ffn_run(h, k, xin, a_rows, counts, offsets, b1, b2, n_rows, yp, workspace, s,
+                                           &policy_advanced);
+    if (rc != MOE_OK && policy_advanced) {
+        // The cache decision already counts the missed experts as resident, but a copy or a launch after it
+        // failed: forget every resident expert, so that the next call loads what it needs instead of running
+        // on slots whose contents never arrived.  (Copies already enqueued finish before the slots are reused:
+        // the next call waits for the caller's stream and orders its copies behind the copy stream's work.)
+        (void)hipStreamSynchronize(k->copy_stream);
+        (void)moe_cache_policy_reset(k->policy);
+    }
+    return rc;
+}
+
+static int buffered_expert_ffn_run(moe_handle_t *h, moe_expert_cache_t *k, const void *xin, const int32_t *a_rows,
+                                   const int32_t *counts, const int32_t *offsets, const void *b1, const void *b2,
+                                   int32_t n_rows, void *yp, void *workspace, hipStream_t s, bool *policy_advanced)
 {
     const moe_config_t &c = h->cfg;
     if (k->h != h) {
@@ -1151,6 +1173,7 @@ static int buffered_expert_ffn(moe_handle_t *h, moe_expert_cache_t *k, const voi
     MOE_HIP_CHECK(hipStreamSynchronize(s));  // also: every earlier call's reads of the slots are over
     int32_t n_loads = 0, n_stages = 0;
     int rc = cache_policy_step(k->policy, h_counts, h_slot, k->stage_of.data(), k->loads.data(), E, &n_loads, &n_stages);
+    *policy_advanced = true;
     if (rc != MOE_OK) return rc;
     // launch index of an expert: 2 * stage for residents, 2 * stage + 1 for the ones copied in this batch
     std::vector<int> in_launch((size_t)2 * (n_stages > 0 ? n_stages : 1), 0);
