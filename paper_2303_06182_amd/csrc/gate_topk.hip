@@ -19,6 +19,12 @@
 // fragment reads on gfx950's 64-bank LDS), the swizzle applied on the global side of the load.  A block
 // is one tile (no persistence: the epilogue is short and there is nothing to keep resident); the tile
 // height is chosen so that the launch still has a tile per CU.
+// (Measured at T = 65536, D = 2048, E = 128 on MI355X: 50 us when x is partly served by the last-level cache,
+// 78 us when every launch reads a different copy of x, about 100 us inside the layer behind the previous
+// step's writes.  A bare read of x in the same order -- a CU owning 256 consecutive rows, no arithmetic --
+// takes 57 us cold, whatever the bytes per row visit (128 B .. 1 KB) or the depth of the prefetch.  A variant
+// that keeps the x rows out of LDS -- each lane loading its own fragments straight into registers four K
+// tiles ahead, only the gate weights staged -- measured the same cold and 20 % slower warm, and was dropped.)
 #include <mutex>
 
 #include "moe_internal.h"
@@ -154,11 +160,14 @@ __global__ __launch_bounds__(WAVES * 64) void gate_topk_kernel(GateTopkParams p)
     auto col_of = [&](int s) { return (s >> 4) * 32 + ((s >> 2) & 3) * 8 + 4 * half + (s & 3); };
     float v[NS];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        const int c = col_of(s);
-        float f = acc[s >> 4][s & 15];
-        if (p.bias) f += (c < E) ? p.bias[c] : 0.f;
-        v[s] = f;
+    for (int s = 0; s < NS; ++s) v[s] = acc[s >> 4][s & 15];
+    if (p.bias) {  // uniform over the grid.  All offsets are requested before the first is added (columns past E read
+                   // the last one): a load per column behind its own predicate makes 16 * NI dependent memory latencies
+        float off[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) off[s] = p.bias[min(col_of(s), E - 1)];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) v[s] += off[s];
     }
     if (p.logits && live) {
         float *dst = p.logits + (int64_t)row * E;
