@@ -107,6 +107,17 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return *reinterpret_cast<const uint32_t *>(&b);
 }
 
+// max(x, 0) on two packed bf16: a bf16 is negative exactly when its bit pattern is negative as a 16-bit integer,
+// so one packed integer max replaces two fp32 compares (and the canonicalisation the compiler puts in front of
+// them); rounding is monotonic and keeps zero, so ReLU after the conversion equals ReLU before it.
+typedef __attribute__((ext_vector_type(2))) short i16x2;
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t packed)
+{
+    const i16x2 zero = {0, 0};
+    const i16x2 r = __builtin_elementwise_max(*reinterpret_cast<const i16x2 *>(&packed), zero);
+    return *reinterpret_cast<const uint32_t *>(&r);
+}
+
 struct TileInfo {
     int row0, row_end, expert, n0;
     int kt0, split;  // plain mode with split K: first K tile and index of this block's K range
@@ -417,7 +428,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                             for (int i = 0; i < 4; ++i) v[i] += bias32[ni][g][i];
                         }
                     }
-                    if (RELU) {
+                    if (RELU && OUT_F32) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.f ? v[i] : 0.f;
                     }
@@ -436,6 +447,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                         uint2 o;
                         o.x = pack_bf16(v[0], v[1]);
                         o.y = pack_bf16(v[2], v[3]);
+                        if (RELU) {
+                            o.x = relu_bf16x2(o.x);
+                            o.y = relu_bf16x2(o.y);
+                        }
                         *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(p.C) + (int64_t)row * p.ldc + col) = o;
                     }
                 }
@@ -499,13 +514,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
 #pragma unroll
                         for (int i = 0; i < 4; ++i) v[i] += p.bias_f32[col + i];
                     }
-                    if (RELU) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.f ? v[i] : 0.f;
-                    }
                     uint2 o;
                     o.x = pack_bf16(v[0], v[1]);
                     o.y = pack_bf16(v[2], v[3]);
+                    if (RELU) {
+                        o.x = relu_bf16x2(o.x);
+                        o.y = relu_bf16x2(o.y);
+                    }
                     const int pos = (cl >> 3) ^ (r & (CPRW - 1));
                     *reinterpret_cast<uint2 *>(stg + r * STRIP_ROW_BYTES + pos * 16 + ((cl >> 2) & 1) * 8) = o;
                 }
