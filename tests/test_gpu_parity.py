@@ -121,6 +121,35 @@ def test_gate_topk_parity(dev, case):
     np.testing.assert_allclose(to_np(gw), rw, rtol=1e-4)
 
 
+@pytest.mark.parametrize("T,D,E,k", [(3000, 256, 128, 2), (700, 128, 37, 3), (40, 512, 64, 2), (500, 72, 16, 2)])
+def test_gate_topk_without_logits_output(dev, T, D, E, k):
+    """logits_out = NULL with a workspace: the decision must not depend on whether the logits are written out
+    (large bf16 batches keep them in registers, the other paths park them in the workspace), and the whole layer
+    must give the same y whether or not any routing array is requested."""
+    w = wl.Workload("nologits", "bf16", T=T, D=D, F=128, E=E, k=k, zipf_s=0.8, zipf_c=0.5, gate_scale=30.0, seed=5)
+    g = cuda(wl.make_inputs(w))
+    m = layer_for(w)
+    logits, idx, gw = m.moe_gate_topk(g["x"], g["wg"], g["gate_bias"])
+    idx2 = torch.full_like(idx, -1)
+    gw2 = torch.full_like(gw, float("nan"))
+    ws, wsb = m._ws()
+    rc = m.lib.moe_gate_topk(m.h, binding._ptr(g["x"]), binding._ptr(g["wg"]), binding._ptr(g["gate_bias"]), T, None,
+                             binding._ptr(idx2), binding._ptr(gw2), ws, wsb, binding._stream())
+    assert rc == binding.MOE_OK
+    # neither logits nor workspace: an argument error, nothing launched
+    rc = m.lib.moe_gate_topk(m.h, binding._ptr(g["x"]), binding._ptr(g["wg"]), None, T, None, binding._ptr(idx2),
+                             binding._ptr(gw2), None, 0, binding._stream())
+    assert rc == binding.MOE_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(gw, gw2)
+    y_all = m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"], routing_out=m.empty_routing(T))
+    y_none = m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"])
+    y_counts = m.moe_layer_forward(g["x"], g["wg"], g["w1"], g["w2"], g["gate_bias"],
+                                   routing_out=dict(counts=torch.empty(E, dtype=torch.int32, device="cuda")))
+    torch.cuda.synchronize()
+    assert torch.equal(y_all, y_none) and torch.equal(y_all, y_counts)
+
+
 # ----------------------------------------------------------------------------- routing
 def random_idx(T, E, k, seed, skew=False):
     rng = np.random.default_rng(seed)
