@@ -232,6 +232,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
         }
         return t;
     };
+    if (GROUPED && !OUT_F32 && p.c_zero_row >= 0 && blockIdx.x == 0 && p.tail_mode != 2) {
+        // one all-zero row behind the output rows, for the GEMM that reads C as its A (N is a multiple of 8)
+        uint16_t *z = static_cast<uint16_t *>(p.C) + (int64_t)p.c_zero_row * p.ldc;
+        for (int i = tid * 8; i < p.N; i += THREADS * 8) *reinterpret_cast<uint4 *>(z + i) = make_uint4(0, 0, 0, 0);
+    }
     if (!seq_ok(seq)) return;
 
     const uint16_t *Ag = static_cast<const uint16_t *>(p.A);
@@ -560,7 +565,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             for (int i = 0; i < A_IT; ++i) {
                 const int r = (wave * A_IT + i) * 8 + (lane >> 3);
                 const int kc = (lane & 7) ^ ((r >> 1) & 7);
-                int gr = min(ti.row0 + r, ti.row_end - 1);  // rows past the end repeat the last one
+                int gr = min(ti.row0 + r, ti.row_end - 1);  // rows past the end repeat the last one ...
+                if (GROUPED && p.a_zero_row >= 0 && ti.row0 + r >= ti.row_end) gr = p.a_zero_row;  // ... or read zeros
                 // dispatch fused into the load: the rows of the expert's batch are gathered straight
                 // from the token array (the launcher checked that rows * lda fits 31 bits)
                 if (GROUPED && p.a_rows) gr = p.a_rows[gr];

@@ -158,7 +158,7 @@ static WsLayout ws_layout(const moe_config_t &c)
     L.num_tiles = take(4);
     L.gate_parts = take((int64_t)(kGateSplitMax - 1) * (T < kGateSplitTokens ? T : kGateSplitTokens) * E * 4);
     L.xp = take(N * c.D * es);
-    L.h = take(N * c.F * es);
+    L.h = take((N + 1) * c.F * es);  // one more row: zeros, read for the padded rows of the second GEMM's tiles
     L.yp = take(N * c.D * es);
     L.total = off;
     return L;
@@ -334,7 +334,7 @@ struct FfnExtra {
     const uint8_t *w2_blk = nullptr;
 };
 
-// Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows, F] and the tile arrays are scratch.
+// Grouped FFN on n_rows rows split by offsets[]; hbuf [n_rows + 1, F] and the tile arrays are scratch.
 static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, const int32_t *offsets,
                           const void *w1, const void *w2, const void *b1, const void *b2, int64_t n_rows, void *yp,
                           void *hbuf, int32_t *tile_expert, int32_t *tile_row, int32_t *num_tiles, hipStream_t s)
@@ -362,6 +362,11 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
     p.num_tiles = num_tiles;
     p.max_m_tiles = max_tiles;
     p.M = (int)n_rows;
+    p.a_zero_row = -1;
+    // The first GEMM leaves a zero row behind H's n_rows rows (hbuf has room for it); the second reads it for the
+    // rows of a tile that lie past the end of an expert's batch.  (Row offsets inside the kernel are 32-bit.)
+    const bool zero_row = c.dtype == MOE_DTYPE_BF16 && (n_rows + 1) * (int64_t)c.F < ((int64_t)1 << 31);
+    p.c_zero_row = zero_row ? (int)n_rows : -1;
     // H = relu(Xp * W1[e]^T + b1[e])
     p.A = xp;
     p.a_rows = ex.a_rows;
@@ -390,6 +395,8 @@ static int run_expert_ffn(moe_handle_t *h, const void *xp, const FfnExtra &ex, c
     // Yp = H * W2[e]^T + b2[e]
     p.A = hbuf;
     p.a_rows = nullptr;
+    p.a_zero_row = zero_row ? (int)n_rows : -1;
+    p.c_zero_row = -1;
     p.lda = c.F;
     p.B = w2;
     p.b_scale = ex.w2_scale;
@@ -472,7 +479,7 @@ static StaticLayout static_layout(const moe_config_t &c, int64_t T, int64_t cap,
     L.tile_row = take(max_tiles * 4);
     L.num_tiles = take(4);
     L.xd = take(R * c.D * es);
-    L.hd = take(R * c.F * es);
+    L.hd = take((R + 1) * c.F * es);
     L.yd = take(R * c.D * es);
     if (mode == MOE_STATIC_EINSUM) {
         L.xt = take((int64_t)c.D * L.ldt * es);

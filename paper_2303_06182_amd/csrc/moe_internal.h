@@ -124,6 +124,12 @@ struct GemmParams {
     // smaller sub-tiles; main_slots = grid size of the launch with tail_mode 1 (both need it)
     int tail_mode;
     int main_slots;
+    // grouped bf16 kernels.  a_zero_row >= 0: row of A's array that is all zero; tile rows past the end of an
+    // expert's batch read it instead of repeating the batch's last row (their results are discarded either way,
+    // but zeros cost the matrix pipes less power than live data, and the clock is power-limited).
+    // c_zero_row >= 0: the launch also writes zeros to that row of C (the next GEMM's a_zero_row).
+    int a_zero_row;
+    int c_zero_row;
     const char *name;            // host only: label of the launch for the event profiler (may be NULL)
 };
 
