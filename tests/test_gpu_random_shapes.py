@@ -11,7 +11,7 @@ from oracle import moe_oracle as orc
 from oracle import quant_e4m3 as o8
 from oracle import quant_mxfp4 as o4
 from paper_2303_06182_amd import binding, workloads as wl
-from helpers import TOL, guarded_inputs, norm_max_err, to_np
+from helpers import RMS_TOL, TOL, guarded_inputs, norm_max_err, rms_rel_err, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -77,5 +77,7 @@ def test_layer_forward_random_shape(c):
     ref = orc.layer_tokens(inp["x"], w1r, w2r, ridx, rw, b1=inp["b1"], b2=inp["b2"])
     got = to_np(y)
     assert np.all(np.isfinite(got))
-    err = norm_max_err(got, ref)
+    err, rms = norm_max_err(got, ref), rms_rel_err(got, ref)
+    print("  err %.3e rms %.3e" % (err, rms), flush=True)
     assert err <= TOL[dtype], err
+    assert rms <= RMS_TOL[dtype], rms
