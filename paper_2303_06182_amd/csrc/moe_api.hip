@@ -796,7 +796,7 @@ static int layer_forward_impl(moe_handle_t *h, moe_expert_cache_t *cache, const 
     rc = do_gate_topk(h, x, wg, gate_bias, T, r.logits, at<float>(workspace, L.logits), idx, w, s,
                       at<float>(workspace, L.gate_parts), block_hist, &hist_tokens);
     if (rc != MOE_OK) return rc;
-    // the routing step's scan kernel also writes the first expert GEMM's tile map (not when the
+    // the routing step's ranking kernel also writes the first expert GEMM's tile map (not when the
     // experts are buffered: their tile maps are per stage)
     const int64_t n_rows = (int64_t)T * c.k;
     const int wbits = cache ? cache->wbits : (w1_blk ? 4 : w1_scale ? 8 : 0);

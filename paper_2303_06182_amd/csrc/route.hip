@@ -471,7 +471,7 @@ __global__ __launch_bounds__(1024) void route_small_kernel(const int32_t *__rest
         start[threadIdx.x] = my_off;
     }
     if (threadIdx.x == 0) offsets[E] = n_assign;
-    if (tile_bm > 0) {  // uniform over the block: the grouped GEMM's M-tile map, as in route_scan_kernel
+    if (tile_bm > 0) {  // uniform over the block: the grouped GEMM's M-tile map, as route_rank_kernel's block 0 writes it
         const int nt = (threadIdx.x < E && cnt > 0) ? (cnt + tile_bm - 1) / tile_bm : 0;
         int incl_t = nt;
 #pragma unroll
