@@ -89,6 +89,8 @@ __device__ __forceinline__ void uniform_load2(const int32_t *pa, const int32_t *
 static constexpr int BK = 64;
 static constexpr int GROUP_M = 4;
 static constexpr int REG_STAGED = 0;  // value of the STAGES template argument that selects the register-staged pipeline
+static constexpr int DTL16 = -1;      // ... and the one that selects 16x16x32 MFMAs out of a ring of K-step slots filled by direct-to-LDS loads
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ uint32_t to_bf16(float f)
 {
@@ -150,11 +152,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
     // STAGES == REG_STAGED selects the register-staged pipeline (two LDS buffers)
     constexpr bool RSTAGE = STAGES == REG_STAGED;
-    constexpr int NSTAGE = RSTAGE ? 2 : STAGES;
+    constexpr bool D16 = STAGES == DTL16;
+    constexpr int NSTAGE = (RSTAGE || D16) ? 2 : STAGES;
     uint16_t *sA = reinterpret_cast<uint16_t *>(smem_raw);  // [NSTAGE][BM*64]
     uint16_t *sB = sA + NSTAGE * BM * BK;                   // [NSTAGE][BN*64]
     static_assert(NSTAGE >= 2, "at least two LDS stages");
     static_assert(!RSTAGE || KFULL, "the register-staged pipeline needs K to be a multiple of the K tile");
+    static_assert(!D16 || (KFULL && BQ == 0 && !OUT_F32), "the 16x16x32 pipeline: bf16 in and out, K a multiple of the K tile");
     static_assert(BQ == 0 || (KFULL && !RSTAGE && GROUPED), "8- and 4-bit weights: grouped direct-to-LDS pipeline, K a multiple of the K tile");
 
     const int tid = threadIdx.x;
@@ -659,6 +663,254 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             __builtin_amdgcn_sched_barrier(0);
         };
         constexpr int LPS = A_IT + B_IT;             // load instructions per wave per stage
+        if constexpr (D16) {
+            // ---- 16x16x32 MFMAs out of a ring of K-step slots filled by direct-to-LDS loads.
+            // Why 16x16x32: v_mfma_f32_16x16x32_bf16 contracts 32 k per accumulator read and write where
+            // v_mfma_f32_32x32x16_bf16 contracts 16; a register-only loop on live data sustains 2.14 PFLOP/s with the
+            // former against 1.93 with the latter under the chip's power limit.  Why direct-to-LDS: ds_write_b128 moves
+            // 64 bytes per clock per CU (measured) where ds_read_b128 moves 256, so writing a K tile's 64 KB from
+            // registers costs the LDS more time than reading its 192 KB of fragments.  Why a ring: a CU takes 64 KB per
+            // K tile through a 64-byte-per-clock path -- half the time the MFMAs of that tile need -- so the loads must
+            // flow evenly, not in a burst per K tile, and they come from HBM or a remote L2 slice.  With two 64 KB
+            // buffers a load can only be issued in the first half of a K tile to land by its end (measured: MFMA pipes
+            // 56 % busy; 68 % when every load hits the L2).  Five slots of ONE K step (32 k: 256 + 256 rows of 64 bytes
+            // = 32 KB; 160 KB in all) let a wave issue one load every eighth MFMA, all the time, each with one to three
+            // steps to land: 66 - 73 % busy at a higher clock.
+            //
+            // Step u multiplies the fragments of slot u mod 5, which were read into registers during step u - 1:
+            //   1. the MFMAs of activation block 0 (their operands landed long ago);
+            //   2. wait for this wave's LDS reads (all of step u's fragments), on odd steps also for its loads of the
+            //      next K tile; barrier.  Behind it every wave's fragments of slot u are in registers, so slots u - 1
+            //      and u are free, and the next K tile has landed for everybody;
+            //   3. the other MFMAs; behind them the reads of step u + 1's fragments from slot u + 1 (the four weight
+            //      fragments into the other register set and block 0 at once, activation block mi in place behind its
+            //      last MFMA) and the loads of the K tile two ahead: both halves of a 16-row group back to back (the
+            //      second request finds the line in the L1 or merges with the first), the first half into slot u + 4,
+            //      the second into slot u + 5 = u.  Loads of a wave land in order, so "at most as many outstanding as
+            //      were issued since" is the wait of point 2.
+            // A slot row is 64 bytes: 16-byte chunk c of row r sits at position c ^ ((r >> 2) & 3), which keeps the 16
+            // lanes x 16 bytes of a fragment read on 16 different bank groups; the permutation is applied on the global
+            // side of the load, inside one 64-byte segment.
+            // Weight row (output column) permutation inside a wave's columns: LDS row 16 * ni + r holds column
+            // 32 * (ni / 2) + 8 * (r / 4) + 4 * (ni % 2) + r % 4, so that the accumulators of blocks 2p and 2p + 1 of a
+            // lane are the 8 consecutive columns 32 p + 8 * (lane / 16) ... of token row lane % 16 and leave as one
+            // 16-byte store, without a trip through LDS (all of which the ring holds).
+            static_assert(GROUPED, "the ring pipeline is instantiated for the grouped GEMM");
+            constexpr int NSLOT = 5;
+            constexpr int SLOT_BYTES = (BM + BN) * 64;
+            constexpr int MI16 = WTM / 16, NI16 = WTN / 16;
+            constexpr int NWAVE = THREADS / 64;
+            constexpr int AG = BM / 16 / NWAVE, BG = BN / 16 / NWAVE;  // 16-row groups a wave loads per K tile
+            constexpr int PAIRS = AG + BG;
+            constexpr int Q1 = PAIRS / 2;                              // pairs issued in the even step; the rest in the odd one
+            constexpr int PB = 1;                                      // activation blocks multiplied in front of the barrier
+            constexpr int PRE = PB * NI16;
+            constexpr int NM16 = MI16 * NI16;
+            constexpr bool ACC16_IN_AGPR = NM16 * 4 > 128;
+            static_assert(BM % (16 * NWAVE) == 0 && BN % (16 * NWAVE) == 0 && WTN % 32 == 0 && MI16 >= 2 && PB < MI16 - 1, "ring pipeline tile shape");
+            static_assert(BK == 64, "a K tile is two steps of 32");
+            f32x4 acc16[MI16][NI16];
+            const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+            const int row16 = lane & 15, kq = lane >> 4;
+            // fragment reads: row (block base + row16), chunk position kq ^ ((row16 >> 2) & 3)
+            const int frag_off = row16 * 64 + ((kq ^ ((row16 >> 2) & 3)) << 4);
+            const uint8_t *fragA = smem_raw + (wm * WTM) * 64 + frag_off;
+            const uint8_t *fragB = smem_raw + BM * 64 + (wn * WTN) * 64 + frag_off;
+            // load stream
+            int l_seq = seq, l_kt = 0;
+            bool l_more = true;
+            int w_slot = 0;  // slot of the first half of the K tile the stream is at
+            const uint8_t *srcA, *srcB;  // same for every lane: the operand's first byte of the stream's K tile
+            uint32_t a_voff[AG][2], b_voff[BG][2];
+            const int ld_row = lane >> 2;                              // row inside the 16-row group
+            const int ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);      // K chunk this lane fetches for its LDS position
+            auto set_ptrs16 = [&](const TileInfo &ti) {
+                const int slot = p.b_slot ? uniform_load(p.b_slot + ti.expert) : ti.expert;
+                srcB = reinterpret_cast<const uint8_t *>(Bg0 + (int64_t)slot * p.strideB);
+                srcA = reinterpret_cast<const uint8_t *>(Ag);
+#pragma unroll
+                for (int g = 0; g < AG; ++g) {
+                    const int r = (wave * AG + g) * 16 + ld_row;
+                    int gr = min(ti.row0 + r, ti.row_end - 1);
+                    if (p.a_zero_row >= 0 && ti.row0 + r >= ti.row_end) gr = p.a_zero_row;
+                    if (p.a_rows) gr = p.a_rows[gr];
+                    const uint32_t o = (uint32_t)gr * (uint32_t)p.lda * 2u + ld_chunk * 16;
+                    a_voff[g][0] = o;
+                    a_voff[g][1] = o + 64;
+                }
+#pragma unroll
+                for (int g = 0; g < BG; ++g) {
+                    const int rho = (wave * BG + g) * 16 + ld_row;  // LDS row of the tile
+                    const int x = rho % WTN, xi = x >> 4, xr = x & 15;
+                    const int c = (rho / WTN) * WTN + 32 * (xi >> 1) + 8 * (xr >> 2) + 4 * (xi & 1) + (xr & 3);
+                    const int gn = min(ti.n0 + c, p.N - 1);
+                    const uint32_t o = (uint32_t)gn * (uint32_t)p.ldb * 2u + ld_chunk * 16;
+                    b_voff[g][0] = o;
+                    b_voff[g][1] = o + 64;
+                }
+            };
+            auto issue_load = [&](int j) {  // load j of the stream's K tile: pair j / 2, K half j % 2
+                const int g = j >> 1, h = j & 1;
+                int slot = w_slot + h;
+                if (slot >= NSLOT) slot -= NSLOT;
+                if (g < AG)
+                    __builtin_amdgcn_global_load_lds((const glb_void *)(srcA + (size_t)l_kt * 128 + a_voff[g][h]),
+                                                     (lds_void *)(smem_raw + slot * SLOT_BYTES + (wave_u * AG + g) * 1024), 16, 0, 0);
+                else
+                    __builtin_amdgcn_global_load_lds((const glb_void *)(srcB + (size_t)l_kt * 128 + b_voff[g - AG][h]),
+                                                     (lds_void *)(smem_raw + slot * SLOT_BYTES + BM * 64 + (wave_u * BG + (g - AG)) * 1024), 16, 0, 0);
+            };
+            auto advance = [&]() {
+                w_slot += 2;
+                if (w_slot >= NSLOT) w_slot -= NSLOT;
+                if (l_more && ++l_kt == KT) {
+                    if (seq_ok(l_seq + slots)) {
+                        l_seq += slots;
+                        l_kt = 0;
+                        set_ptrs16(tile_info(l_seq));
+                    } else {
+                        l_more = false;
+                        l_kt = KT - 1;  // past the end: re-read the last K tile into slots nobody reads
+                    }
+                }
+            };
+            // a16[MI16 - 1 + P]: the last activation block has a register set per step parity, so that its read for the
+            // next step goes out with the first ones and the step's last LDS read is four MFMAs from the step's end
+            bf16x8 a16[MI16 + 1], w16[2][NI16];
+            int r_slot = 0;  // slot of the step being multiplied
+            auto read_frag = [&](const uint8_t *base, int slot, int block) {
+                return *reinterpret_cast<const bf16x8 *>(base + slot * SLOT_BYTES + block * 1024);
+            };
+            auto step = [&](auto parity) {
+                constexpr int P = decltype(parity)::value;
+                constexpr int NL = P == 0 ? 2 * Q1 : 2 * (PAIRS - Q1);  // loads issued in this step
+                constexpr int J0 = P == 0 ? 0 : 2 * Q1;
+                constexpr int GAP = NL > 0 ? ((NM16 - PRE) / NL > 8 ? 8 : (NM16 - PRE) / NL) : 1;  // MFMAs between two loads
+                static_assert(NL == 0 || GAP >= 1, "more loads than MFMA slots behind the barrier");
+                auto mfma = [&](int mi, int ni) {
+                    acc16[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w16[P][ni], a16[mi == MI16 - 1 ? mi + P : mi], acc16[mi][ni], 0, 0, 0);
+                };
+#pragma unroll
+                for (int mi = 0; mi < PB; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni) mfma(mi, ni);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("" ::: "memory");
+                // lgkmcnt(0); odd steps: at most the loads of the even step before may be outstanding
+                if (P == 1)
+                    __builtin_amdgcn_s_waitcnt(0x0070 | ((2 * Q1) & 15) | (((2 * Q1) >> 4) << 14));
+                else
+                    __builtin_amdgcn_s_waitcnt(0xc07f);
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                const int nslot = r_slot + 1 == NSLOT ? 0 : r_slot + 1;
+#pragma unroll
+                for (int ni = 0; ni < NI16; ++ni) w16[P ^ 1][ni] = read_frag(fragB, nslot, ni);
+#pragma unroll
+                for (int mi = 0; mi < PB; ++mi) a16[mi] = read_frag(fragA, nslot, mi);
+                a16[MI16 - 1 + (P ^ 1)] = read_frag(fragA, nslot, MI16 - 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mi = PB; mi < MI16; ++mi) {
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni) {
+                        const int gm = mi * NI16 + ni;
+                        mfma(mi, ni);
+                        if (ni == NI16 - 1 && mi < MI16 - 1) a16[mi] = read_frag(fragA, nslot, mi);
+                        if (NL > 0 && (gm - PRE) % GAP == 0 && (gm - PRE) / GAP < NL) issue_load(J0 + (gm - PRE) / GAP);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                r_slot = nslot;
+                if (P == (Q1 == PAIRS ? 0 : 1)) advance();  // behind the K tile's last load
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            auto epilogue16 = [&](const TileInfo &ti) {
+                const uint16_t *bias = static_cast<const uint16_t *>(p.bias);
+                if (bias) bias += (int64_t)ti.expert * p.strideBias;
+                const int col_base = ti.n0 + wn * WTN + 8 * kq;
+                uint8_t *const cbase = static_cast<uint8_t *>(p.C);
+                const uint32_t row_step = 16u * (uint32_t)p.ldc * 2u;  // bytes between two row blocks
+                auto store_all = [&](auto with_bias) {
+#pragma unroll
+                    for (int pp = 0; pp < NI16 / 2; ++pp) {
+                        const int col = col_base + 32 * pp;
+                        uint32_t bw[4] = {0, 0, 0, 0};
+                        if (decltype(with_bias)::value && col < p.N) {  // N is a multiple of 8
+                            const uint4 bb = *reinterpret_cast<const uint4 *>(bias + col);
+                            bw[0] = bb.x, bw[1] = bb.y, bw[2] = bb.z, bw[3] = bb.w;
+                        }
+                        const int row0 = ti.row0 + wm * WTM + row16;
+                        uint32_t off = (uint32_t)row0 * (uint32_t)p.ldc * 2u + (uint32_t)col * 2u;  // the launcher checked that C fits 32 bits
+#pragma unroll
+                        for (int mi = 0; mi < MI16; ++mi) {
+                            uint32_t o[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {  // columns 2q, 2q + 1 of the 8: block 2pp + q / 2, registers 2 (q % 2), + 1
+                                float v0, v1;
+                                if constexpr (ACC16_IN_AGPR) {  // read in place, as in the 32x32 epilogue
+                                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v0) : "a"(acc16[mi][2 * pp + (q >> 1)][2 * (q & 1)]));
+                                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v1) : "a"(acc16[mi][2 * pp + (q >> 1)][2 * (q & 1) + 1]));
+                                } else {
+                                    v0 = acc16[mi][2 * pp + (q >> 1)][2 * (q & 1)], v1 = acc16[mi][2 * pp + (q >> 1)][2 * (q & 1) + 1];
+                                }
+                                if (decltype(with_bias)::value) {
+                                    v0 += __uint_as_float(bw[q] << 16);
+                                    v1 += __uint_as_float(bw[q] & 0xffff0000u);
+                                }
+                                o[q] = pack_bf16(v0, v1);
+                                if (RELU) o[q] = relu_bf16x2(o[q]);
+                            }
+                            if (row0 + mi * 16 < ti.row_end && col < p.N)
+                                *reinterpret_cast<uint4 *>(cbase + off) = make_uint4(o[0], o[1], o[2], o[3]);
+                            off += row_step;
+                        }
+                    }
+                };
+                if constexpr (ACC16_IN_AGPR) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+                if (bias)
+                    store_all(std::true_type{});
+                else
+                    store_all(std::false_type{});
+            };
+            // prologue: the first two K tiles of the stream -> slots 0..3; fragments of step 0
+            set_ptrs16(t);
+#pragma unroll
+            for (int rep = 0; rep < 2; ++rep) {
+#pragma unroll
+                for (int j = 0; j < 2 * PAIRS; ++j) issue_load(j);
+                advance();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0x0f70 | ((2 * PAIRS) & 15) | (((2 * PAIRS) >> 4) << 14));  // the first K tile has landed
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ni = 0; ni < NI16; ++ni) w16[0][ni] = read_frag(fragB, 0, ni);
+#pragma unroll
+            for (int mi = 0; mi < MI16; ++mi) a16[mi] = read_frag(fragA, 0, mi);  // step 0 is even: its last block is a16[MI16 - 1]
+            while (true) {
+#pragma unroll
+                for (int mi = 0; mi < MI16; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc16[mi][ni][r] = 0.f;
+                for (int kt = 0; kt < KT; ++kt) {
+                    step(std::integral_constant<int, 0>{});
+                    step(std::integral_constant<int, 1>{});
+                }
+                epilogue16(t);
+                seq += slots;
+                if (!seq_ok(seq)) break;
+                t = tile_info(seq);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no LDS write may outlive the block
+            return;
+        }
         if constexpr (RSTAGE) {
             // ---- register-staged pipeline.  A vector-memory instruction costs the issuing wave
             // about one MFMA slot and the CU's address unit 16 clocks, so the loads of a K tile
@@ -940,8 +1192,9 @@ static int launch_k(const GemmParams &p_in, int num_cus, hipStream_t s, int *mai
     const int n_tiles = ceil_div(p.N, BN);
     const int m_tiles = GROUPED ? p.max_m_tiles : ceil_div(p.M, BM);
     if (m_tiles <= 0 || n_tiles <= 0) return MOE_OK;
-    const size_t smem = (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (BQ == 8 ? BN / 2 : BQ == 4 ? BN / 4 : BN)) * BK * sizeof(uint16_t) +
-                        (BQ == 4 ? 2 * BN * 16 : 0);  // 4-bit weights: two buffers of block scales
+    const size_t smem = STAGES == DTL16 ? (size_t)5 * (BM + BN) * 64  // five slots of one 32-wide K step
+                                        : (size_t)(STAGES == REG_STAGED ? 2 : STAGES) * (BM + (BQ == 8 ? BN / 2 : BQ == 4 ? BN / 4 : BN)) * BK * sizeof(uint16_t) +
+                                              (BQ == 4 ? 2 * BN * 16 : 0);  // 4-bit weights: two buffers of block scales
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, OUT_F32, RELU, GROUPED, KFULL, MINB, STAGES, BQ>;
     // per instantiation, once, whichever host thread comes first: the LDS size attribute and the occupancy
     static std::once_flag once;
@@ -1114,7 +1367,12 @@ int launch_gemm_bf16(const GemmParams &p, bool grouped, int variant, bool out_f3
         GemmParams q = p;
         int main_grid = 0;
         q.tail_mode = 1;
-        int rc = launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(q, relu, num_cus, s, &main_grid);
+        // the ring pipeline addresses both operands with 32-bit byte offsets from one base
+        const int64_t a_rows_max = (int64_t)(p.a_zero_row >= p.M ? p.a_zero_row + 1 : p.M);
+        const bool ring_ok = a_rows_max * p.lda * 2 < (1ll << 32) && (int64_t)p.N * p.ldb * 2 < (1ll << 32) &&
+                             ((int64_t)(p.c_zero_row >= p.M ? p.c_zero_row + 1 : p.M) + 256) * p.ldc * 2 < (1ll << 32);
+        int rc = ring_ok ? launch_grouped<256, 256, 2, 4, 1, DTL16>(q, relu, num_cus, s, &main_grid)
+                         : launch_grouped<256, 256, 2, 4, 1, REG_STAGED>(q, relu, num_cus, s, &main_grid);
         if (rc != MOE_OK || main_grid == 0) return rc;
         q.tail_mode = 2;
         return launch_grouped<128, 128, 2, 2, 2, REG_STAGED>(q, relu, num_cus, s, &main_grid);

@@ -271,6 +271,11 @@ FFN_CASES = [
     ("bf16", [1100, 0, 900, 257, 1500, 640, 3, 700], 256, 3328, False),
     # 24 x 17 = 408 tiles: the 152 leftover tiles are too many for the tail launch, two main rounds
     ("bf16", [1100, 0, 900, 257, 1500, 640, 3, 700], 256, 4352, True),
+    # 256-row tiles whose last column tile is partly outside the matrix, in both GEMMs (F = 12.5, D = 11.25 column
+    # tiles; 24 x 13 and 24 x 12 tiles: a whole round each in the main launch), with offsets
+    ("bf16", [1100, 0, 900, 257, 1500, 640, 3, 700], 2880, 3200, True),
+    # a single K tile per output tile in the first GEMM (the load stream changes tile after every K tile)
+    ("bf16", [1100, 0, 900, 257, 1500, 640, 3, 700], 64, 3328, False),
 ]
 
 
