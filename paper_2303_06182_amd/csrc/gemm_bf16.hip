@@ -833,18 +833,23 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                 uint8_t *const cbase = static_cast<uint8_t *>(p.C);
                 const uint32_t row_step = 16u * (uint32_t)p.ldc * 2u;  // bytes between two row blocks
                 auto store_all = [&](auto with_bias) {
+                    constexpr bool BIAS = decltype(with_bias)::value;
+                    uint32_t bw[NI16 / 2][4] = {};
+                    if constexpr (BIAS) {
 #pragma unroll
-                    for (int pp = 0; pp < NI16 / 2; ++pp) {
-                        const int col = col_base + 32 * pp;
-                        uint32_t bw[4] = {0, 0, 0, 0};
-                        if (decltype(with_bias)::value && col < p.N) {  // N is a multiple of 8
-                            const uint4 bb = *reinterpret_cast<const uint4 *>(bias + col);
-                            bw[0] = bb.x, bw[1] = bb.y, bw[2] = bb.z, bw[3] = bb.w;
-                        }
-                        const int row0 = ti.row0 + wm * WTM + row16;
-                        uint32_t off = (uint32_t)row0 * (uint32_t)p.ldc * 2u + (uint32_t)col * 2u;  // the launcher checked that C fits 32 bits
+                        for (int pp = 0; pp < NI16 / 2; ++pp)
+                            if (col_base + 32 * pp < p.N) {  // N is a multiple of 8
+                                const uint4 bb = *reinterpret_cast<const uint4 *>(bias + col_base + 32 * pp);
+                                bw[pp][0] = bb.x, bw[pp][1] = bb.y, bw[pp][2] = bb.z, bw[pp][3] = bb.w;
+                            }
+                    }
+                    const int row0 = ti.row0 + wm * WTM + row16;
+                    uint32_t off = (uint32_t)row0 * (uint32_t)p.ldc * 2u + (uint32_t)col_base * 2u;  // the launcher checked that C fits 32 bits
 #pragma unroll
-                        for (int mi = 0; mi < MI16; ++mi) {
+                    for (int mi = 0; mi < MI16; ++mi) {
+                        // the column pairs of a row block back to back: together they fill whole 128-byte lines
+#pragma unroll
+                        for (int pp = 0; pp < NI16 / 2; ++pp) {
                             uint32_t o[4];
 #pragma unroll
                             for (int q = 0; q < 4; ++q) {  // columns 2q, 2q + 1 of the 8: block 2pp + q / 2, registers 2 (q % 2), + 1
@@ -855,17 +860,17 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
                                 } else {
                                     v0 = acc16[mi][2 * pp + (q >> 1)][2 * (q & 1)], v1 = acc16[mi][2 * pp + (q >> 1)][2 * (q & 1) + 1];
                                 }
-                                if (decltype(with_bias)::value) {
-                                    v0 += __uint_as_float(bw[q] << 16);
-                                    v1 += __uint_as_float(bw[q] & 0xffff0000u);
+                                if constexpr (BIAS) {
+                                    v0 += __uint_as_float(bw[pp][q] << 16);
+                                    v1 += __uint_as_float(bw[pp][q] & 0xffff0000u);
                                 }
                                 o[q] = pack_bf16(v0, v1);
                                 if (RELU) o[q] = relu_bf16x2(o[q]);
                             }
-                            if (row0 + mi * 16 < ti.row_end && col < p.N)
-                                *reinterpret_cast<uint4 *>(cbase + off) = make_uint4(o[0], o[1], o[2], o[3]);
-                            off += row_step;
+                            if (row0 + mi * 16 < ti.row_end && col_base + 32 * pp < p.N)
+                                *reinterpret_cast<uint4 *>(cbase + off + 64 * pp) = make_uint4(o[0], o[1], o[2], o[3]);
                         }
+                        off += row_step;
                     }
                 };
                 if constexpr (ACC16_IN_AGPR) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
