@@ -18,8 +18,11 @@
 // different chunk positions, so fragment reads are conflict free (measured: 4 clk per
 // ds_read_b128 against 6 clk with an (r & 7) swizzle).
 //
-// Two K pipelines, chosen per tile shape (template argument STAGES):
-//  * direct-to-LDS (small tiles, the gate): STAGES LDS stages; K tiles go straight from global
+// Three K pipelines, chosen per tile shape (template argument STAGES):
+//  * ring of K steps (the 256x256 tiles of the grouped GEMM, STAGES = DTL16): v_mfma_f32_16x16x32_bf16
+//    instead of the 32x32 blocks, operands straight into LDS, five slots of one 32-wide K step, one
+//    load every seventh MFMA; described where it is implemented, inside the kernel.
+//  * direct-to-LDS, whole K tiles (small tiles, the gate): STAGES LDS stages; K tiles go straight from global
 //    memory into LDS (global_load_lds_dwordx4, no register staging), the loads run STAGES-1 K
 //    tiles ahead of the MFMAs and are waited for (vmcnt) only at the barrier that ends an
 //    iteration.  Several such blocks share a CU, so one block's load burst and barrier hide
@@ -32,11 +35,11 @@
 //    are written to the other LDS buffer at the same slot of iteration i+1 and the register is
 //    refilled at once: every load has a full iteration to land and the address unit sees an
 //    even stream.
-// In both, the fragments of K-step ks+1 are read while the MFMAs of K-step ks issue (the
+// In the last two, the fragments of K-step ks+1 are read while the MFMAs of K-step ks issue (the
 // instruction order is pinned with sched_group_barrier / sched_barrier, otherwise the compiler
 // sinks the reads next to their use).
 //
-// Epilogue (bf16 output): each wave converts a 32-row strip of its tile, parks it in the LDS rows
+// Epilogue (bf16 output, last two pipelines): each wave converts a 32-row strip of its tile, parks it in the LDS rows
 // only this wave's loads ever fill, and writes it out with 16 bytes per lane, i.e. whole
 // contiguous row segments per store instruction; the scattered form (16 bytes per row per
 // instruction) cost up to a fifth of a tile's time.
