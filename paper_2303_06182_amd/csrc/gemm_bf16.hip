@@ -21,7 +21,7 @@
 // Three K pipelines, chosen per tile shape (template argument STAGES):
 //  * ring of K steps (the 256x256 tiles of the grouped GEMM, STAGES = DTL16): v_mfma_f32_16x16x32_bf16
 //    instead of the 32x32 blocks, operands straight into LDS, five slots of one 32-wide K step, one
-//    load every seventh MFMA; described where it is implemented, inside the kernel.
+//    load every seventh MFMA (four per step); described where it is implemented, inside the kernel.
 //  * direct-to-LDS, whole K tiles (small tiles, the gate): STAGES LDS stages; K tiles go straight from global
 //    memory into LDS (global_load_lds_dwordx4, no register staging), the loads run STAGES-1 K
 //    tiles ahead of the MFMAs and are waited for (vmcnt) only at the barrier that ends an
@@ -677,7 +677,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINB) void gemm_bf16_kernel(GemmParams
             // flow evenly, not in a burst per K tile, and they come from HBM or a remote L2 slice.  With two 64 KB
             // buffers a load can only be issued in the first half of a K tile to land by its end (measured: MFMA pipes
             // 56 % busy; 68 % when every load hits the L2).  Five slots of ONE K step (32 k: 256 + 256 rows of 64 bytes
-            // = 32 KB; 160 KB in all) let a wave issue one load every eighth MFMA, all the time, each with one to three
+            // = 32 KB; 160 KB in all) let a wave issue four loads per step, seven MFMAs apart, all the time, each with one to three
             // steps to land: 66 - 73 % busy at a higher clock.
             //
             // Step u multiplies the fragments of slot u mod 5, which were read into registers during step u - 1:
