@@ -418,6 +418,16 @@ def test_layer_forward_with_biases_and_raw_softmax(dev):
 FULL = [("tiny_f32", None), ("lm", None), ("mt_encoder", None), ("mt_decoder", None), ("skewed_large", 8192)]
 
 
+def test_layer_forward_large_tiles_with_odd_dimensions(dev):
+    """A mid-size layer on the 256-row tiles' main launch (8 experts with about 5000 rows each: 160 row tiles x 13
+    and x 2 column tiles) whose dimensions are not multiples of the tile: D = 320 (five K tiles, a column tile and
+    a quarter in the second GEMM), F = 3200 (12.5 column tiles in the first GEMM, 50 K tiles in the second), with
+    offsets in both GEMMs and the rows of the first gathered from x; every token compared."""
+    w = wl.CONFIGS["mt_encoder"].scaled(name="ring_odd", T=20000, D=320, F=3200, E=8)
+    say("layer large tiles, odd dimensions", w)
+    run_layer_and_check(w, with_ffn_bias=True, device="cuda")
+
+
 @pytest.mark.parametrize("name,sample", FULL, ids=[f[0] for f in FULL])
 def test_layer_forward_full_size(dev, name, sample):
     """The five benchmark workloads at full size: routing bit-exact for every token; output compared on every
