@@ -534,7 +534,7 @@ def test_argument_errors(dev):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("kind", ["bf16_mid", "bf16_decoder", "w8_decoder", "w4_decoder"])
+@pytest.mark.parametrize("kind", ["bf16_mid", "bf16_large_tiles", "bf16_decoder", "w8_decoder", "w4_decoder"])
 def test_layer_forward_can_be_captured_in_a_graph(dev, kind):
     """The fused call only enqueues kernels on the caller's stream (no allocation, no host wait,
     no memset node), so it can be recorded into a HIP graph; every replay, with eager work and
@@ -543,6 +543,9 @@ def test_layer_forward_can_be_captured_in_a_graph(dev, kind):
     quantised expert GEMMs through the same check."""
     if kind == "bf16_mid":
         w = wl.CONFIGS["lm"].scaled(name="graph", T=1500, D=256, F=512, E=16)
+    elif kind == "bf16_large_tiles":
+        # 256-row tiles: main launch (the ring-of-K-steps kernel, all of the CU's LDS) and tail launch in the graph
+        w = wl.CONFIGS["mt_encoder"].scaled(name="graph_large", T=6000, D=256, F=3328, E=8)
     else:
         w = wl.CONFIGS["mt_decoder"].scaled(name="graph_dec", D=512, F=1024, E=32)
     g = cuda(wl.make_inputs(w))
