@@ -82,6 +82,13 @@ def test_buffered_many_tokens_and_skew(dev):
     run_trace(w, [3, 16], n_steps=3)
 
 
+def test_buffered_large_tiles(dev):
+    # stages of three experts with 3000 rows each: 36 row tiles x 13 column tiles per stage, i.e. the 256-row
+    # tiles' main launch reads its weights through the slot table; bit-identical to the resident call
+    w = wl.CONFIGS["mt_encoder"].scaled(name="enc_mid", T=12000, D=256, F=3328, E=8)
+    run_trace(w, [3, 8], n_steps=2)
+
+
 def test_buffered_empty_batch_and_errors(dev):
     w = wl.CONFIGS["mt_decoder"].scaled(name="dec_small", T=8, D=64, F=128, E=8)
     inp = wl.make_inputs(w)
